@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the streaming denoiser hot path on one MI355X.
+
+A "step" is one sdv2_denoise_step call: timestep conditioning plus every block of the model on one
+chunk of synthetic input, with all inputs, weights and caches already resident in HBM.  The default
+workload is the 1.3B-shaped model (30 blocks) at steady state (sink full, window full, so every
+step evicts), one denoising step per chunk.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Timing: W warm-up steps, then K steps between two torch.cuda.synchronize() calls and a pair of
+events on the stream the library launches on (value = the slower of wall clock and events is not
+taken: value is the event time; the wall time is reported beside it).  A second pass over K more
+steps runs with the library's per-launch event timing switched on and yields the per-kernel
+durations used for the roofline object.  The oracle is then timed on the host cores on one step.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--workload", default="wan1.3b-step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=0, help="blocks the oracle times (0: all, bounded to ~30 s)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2511_07399_amd import binding, cost_model as cm, workloads as wk
+
+    from paper_2511_07399_amd.runner import DeviceModel
+
+    binding.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = wk.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    B, L, Cw = wl.B, wl.L, wl.C
+    gpu = DeviceModel(wl, base_seed=0, device=dev, weight_device=dev)
+    frames = wl.frames_per_chunk
+    n_inputs = 8
+    xs = [torch.stack([wk.chunk_input(wl, c, s, device=dev) for s in range(B)]).contiguous() for c in range(n_inputs)]
+    stream = torch.cuda.current_stream()
+
+    # fill the caches so that the timed steps run at steady state (every chunk evicts)
+    fill_chunks = (wl.sink_frames + wl.window_frames + frames - 1) // frames + 1
+    chunk = 0
+
+    def one_step(c):
+        x = xs[c % n_inputs].clone()
+        descs = [(s, c * frames, frames, 1) for s in range(B)]
+        ts = [wk.timestep(wl, c, 0, s) for s in range(B)]
+        return x, descs, ts
+
+    for _ in range(fill_chunks + args.warmup):
+        x, descs, ts = one_step(chunk)
+        gpu.denoise(x, descs, timesteps=ts)
+        chunk += 1
+    torch.cuda.synchronize()
+    st = gpu.state(0, 0)
+    assert st["win_fill"] == wl.W and st["evicted"] > 0, "not at steady state"
+    l_kv = st["sink_fill"] + st["win_fill"]
+
+    # ---- pass 1: the headline number
+    prepared = [one_step(chunk + i) for i in range(args.steps)]
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for x, descs, ts in prepared:
+        gpu.denoise(x, descs, timesteps=ts)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    chunk += args.steps
+    assert all(torch.isfinite(x).all().item() for x, _, _ in prepared[-2:])
+
+    # ---- pass 2: same steps again with per-launch events
+    n_launch = args.steps * wl.N * len(binding.LAUNCH_TAGS)
+    prepared = [one_step(chunk + i) for i in range(args.steps)]
+    torch.cuda.synchronize()
+    binding.prof_begin(n_launch)
+    for x, descs, ts in prepared:
+        gpu.denoise(x, descs, timesteps=ts)
+    samples = binding.prof_end(n_launch)
+    chunk += args.steps
+    per_tag = {}
+    for tag, ms in samples:
+        per_tag.setdefault(tag, []).append(ms)
+    rows = B * L
+    flops = {
+        1: cm.gemm_flops(rows, 3 * Cw, Cw), 4: cm.gemm_flops(rows, Cw, Cw), 6: cm.gemm_flops(rows, Cw, Cw),
+        9: cm.gemm_flops(rows, Cw, Cw), 11: cm.gemm_flops(rows, wl.F, Cw), 12: cm.gemm_flops(rows, Cw, wl.F),
+        3: cm.attention_flops(rows, l_kv, Cw), 8: cm.attention_flops(rows, wl.L_t, Cw),
+    }
+    hbm_bytes = {
+        0: rows * Cw * (4 + 2), 5: rows * Cw * (4 + 2), 10: rows * Cw * (4 + 2),      # fp32 x in, bf16 h out
+        2: rows * Cw * 2 * (3 + 3), 7: rows * Cw * 2 * 2,                              # qkv in; q, k, v out
+    }
+    kernels = {}
+    for tag, vals in sorted(per_tag.items()):
+        avg_us = float(np.mean(vals)) * 1e3
+        entry = {"avg_us": round(avg_us, 2), "launches": len(vals)}
+        if tag in flops:
+            entry["tflops"] = round(flops[tag] / (avg_us * 1e-6) / 1e12, 1)
+            entry["frac_mfma_peak"] = round(flops[tag] / (avg_us * 1e-6) / cm.MI355X_BF16_FLOPS, 4)
+        if tag in hbm_bytes:
+            entry["gbps"] = round(hbm_bytes[tag] / (avg_us * 1e-6) / 1e9, 1)
+            entry["frac_hbm_peak"] = round(hbm_bytes[tag] / (avg_us * 1e-6) / cm.MI355X_HBM_BW, 4)
+        kernels[binding.LAUNCH_TAGS[tag]] = entry
+    gemm_tags = (1, 4, 6, 9, 11, 12)
+    attn_tags = (3, 8)
+    sum_us = lambda tags: sum(float(np.mean(per_tag[t])) * 1e3 for t in tags if t in per_tag)
+    gemm_tflops = sum(flops[t] for t in gemm_tags) / (sum_us(gemm_tags) * 1e-6) / 1e12
+    attn_tflops = sum(flops[t] for t in attn_tags) / (sum_us(attn_tags) * 1e-6) / 1e12
+    # dominant kernel: the FFN-1 GEMM launch site (largest share of the block's flops)
+    dom = 11
+    dom_us = float(np.mean(per_tag[dom])) * 1e3
+    achieved = flops[dom] / (dom_us * 1e-6) / 1e12
+    roofline = {
+        "bound": "mfma", "kernel": "gemm_kernel @ FFN-1 (M=%d, N=%d, K=%d, bf16)" % (rows, wl.F, Cw),
+        "achieved": round(achieved, 1), "peak": cm.MI355X_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
+        "frac": round(achieved * 1e12 / cm.MI355X_BF16_FLOPS, 4), "avg_launch_us": round(dom_us, 2),
+        "flops_per_launch": flops[dom], "traffic": None,
+    }
+    step_flops = wl.N * cm.block_flops(rows, Cw, wl.F, l_kv, wl.L_t)
+
+    # ---- oracle on the host cores (a reported baseline, not the target)
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = time_oracle(wl, args.cpu_layers)
+
+    out = {
+        "metric": "per-chunk denoise-step latency", "value": round(ms_per_step, 4), "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": "%s: %d blocks, C %d, %d heads x 128, FFN %d, %d stream(s) x %d query tokens per chunk, "
+                        "sink %d + window %d tokens (steady state, L_kv %d), %d text tokens, 1 denoising step per "
+                        "chunk, fp32 residual stream" % (wl.name, wl.N, Cw, wl.H, wl.F, B, L, wl.S, wl.W, l_kv, wl.L_t),
+            "global_batch": B, "seq_len": L,
+        },
+        "wall_ms_per_step": round(wall_ms, 4),
+        "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
+        "step_frac_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / cm.MI355X_BF16_FLOPS, 4),
+        "gemm_tflops": round(gemm_tflops, 1), "attn_tflops": round(attn_tflops, 1),
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
+    }
+    gpu.close()
+    print(json.dumps(out))
+
+
+def time_oracle(wl, n_layers_req):
+    """Wall clock of the oracle's denoise step at steady state on the host cores.
+
+    Layers are timed one after the other so that only one layer's float64 weights are alive; the
+    caches are pre-filled with random history (untimed) so that the step attends over a full
+    window.  If the model has more layers than fit ~30 s, the first layers are timed and scaled.
+    """
+    import numpy as np
+    import oracle
+    from paper_2511_07399_amd import workloads as wk
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    flops_block = wl.block_flops() / wl.B
+    budget_flops = 25.0 * 250e9          # ~25 s at the ~250 GFLOP/s float64 BLAS rate of a 16-core share
+    n_layers = n_layers_req or max(1, min(wl.N, int(budget_flops / flops_block)))
+    mw = wk.to_numpy(wk.model_weights(wl))
+    t = wk.timestep(wl, 0)
+    x = wk.chunk_input(wl, 0).double().numpy()
+    t_start = time.perf_counter()
+    e0 = oracle.conditioning(mw, t=t)
+    timed = time.perf_counter() - t_start
+    rng = np.random.default_rng(0)
+    for layer in range(n_layers):
+        w = wk.to_numpy(wk.block_weights(wl, layer))
+        ctx = wk.text_context(wl).double().numpy()
+        tk, tv = oracle.text_kv_prepare(ctx, w)
+        cache = oracle.RollingKVCache(wl.S, wl.W, wl.P, wl.C)
+        done = 0
+        while done < wl.S + wl.W:          # random history, untimed
+            n = min(wl.L, wl.W)
+            cache.append_evict(rng.standard_normal((n, wl.C)), rng.standard_normal((n, wl.C)))
+            done += n
+        t_start = time.perf_counter()
+        x = oracle.dit_block_forward(x, e0, w, cache, tk, tv, wl.H, wl.P, wl.grid_w, frame_pos0=100)
+        timed += time.perf_counter() - t_start
+    scale = wl.N / n_layers
+    ms = timed * 1e3 * scale * wl.B
+    return {
+        "value": round(ms, 1), "unit": "ms", "cores": cores, "kind": "oracle",
+        "sample": "oracle (numpy float64) denoise step at steady state, %d of %d blocks timed on one stream%s"
+                  % (n_layers, wl.N, "" if n_layers == wl.N and wl.B == 1 else
+                     ", scaled x%.2f to %d blocks x %d stream(s)" % (scale * wl.B, wl.N, wl.B)),
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,300 @@
+/*
+ * sdv2.h - C ABI of libsdv2: the streaming causal video-DiT block for one chunk
+ * on one MI355X (gfx950), with a sink-token-guided rolling KV cache.
+ *
+ * The calls follow StreamDiffusionV2's statement of the streaming problem: an
+ * unbounded sequence of short chunks per stream (Section 1, "Efficiency
+ * objectives"; Section 3), each denoised in 1-4 steps (Section 5.1) by a causal
+ * DiT (Section 5.1 "Models") against a per-layer cache made of sink tokens and
+ * a rolling window of recent frames that is updated frame by frame (abstract;
+ * Section 1; Appendix D, rolling-KV-cache figure), with B independent streams
+ * batched through one forward (Section 4.1, SLO-aware batching scheduler).
+ * The per-layer work is the one Appendix B costs: projections and FFN
+ * (24 b L_q C^2 flops) and attention over the cache (4 b L_q L_kv C flops).
+ *
+ * General rules
+ *  - Every function returns 0 (SDV2_OK) or a negative sdv2_status; the text of
+ *    the last error of the calling thread is at sdv2_last_error().
+ *  - All arguments are validated before anything is launched or any state is
+ *    changed: a failed call leaves cache state and device memory untouched.
+ *  - "dev" pointers are device memory owned by the caller; "host" pointers are
+ *    ordinary host memory.  The library never allocates or frees device memory
+ *    and never synchronises: work is enqueued on the caller's hipStream_t
+ *    (passed as void*; NULL is the default stream).
+ *  - Matrices are bf16, row-major, stored [out, in] (y = x W^T + b); vectors
+ *    (biases, gains, modulation tables) are fp32.  The hidden state x is fp32.
+ *  - Head h owns columns [h*128, (h+1)*128) of a token row; head_dim is 128.
+ *  - Calls that touch the same cache, x or workspace must be ordered by the
+ *    caller (same stream); ring positions are tracked on the host in call order.
+ */
+#ifndef SDV2_H
+#define SDV2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SDV2_MAX_BATCH 8      /* streams per dit_block_forward / denoise_step call */
+#define SDV2_HEAD_DIM 128
+
+typedef enum sdv2_status {
+    SDV2_OK = 0,
+    SDV2_INVALID_ARG = -1,          /* null pointer, bad size, size not a multiple of what is required */
+    SDV2_BAD_STATE = -2,            /* e.g. advance = 0 without a previous append of the same size */
+    SDV2_WORKSPACE_TOO_SMALL = -3,
+    SDV2_HIP_ERROR = -4             /* a launch failed; the text names the HIP error */
+} sdv2_status;
+
+/* Shape of the model.  Set struct_size = sizeof(sdv2_model_cfg). */
+typedef struct sdv2_model_cfg {
+    uint32_t struct_size;
+    int32_t C;            /* model width, = n_heads * 128, multiple of 128, <= 8192 */
+    int32_t n_heads;
+    int32_t ffn_dim;      /* multiple of 128 */
+    int32_t grid_h;       /* token rows per latent frame */
+    int32_t grid_w;       /* token columns per latent frame; tokens_per_frame = grid_h * grid_w */
+    int32_t text_len;     /* text tokens L_t (> 0) */
+    int32_t n_layers;
+    int32_t t_dim;        /* width of the sinusoidal timestep embedding (even, multiple of 8; 256) */
+    float eps;            /* LayerNorm / RMSNorm epsilon (1e-6) */
+    float rope_base;      /* 10000 */
+} sdv2_model_cfg;
+
+/* Shape of the cache.  All capacities in tokens and whole frames. */
+typedef struct sdv2_cache_cfg {
+    uint32_t struct_size;
+    int32_t n_layers;
+    int32_t n_streams;
+    int32_t n_heads;
+    int32_t tokens_per_frame;
+    int32_t sink_tokens;      /* S >= 0: the first S tokens of a stream, never evicted */
+    int32_t window_tokens;    /* W > 0: ring of the most recent tokens, the current chunk included */
+} sdv2_cache_cfg;
+
+/* One layer's parameters (all dev pointers). */
+typedef struct sdv2_block_weights {
+    uint32_t struct_size;
+    uint32_t reserved;
+    const void* W_qkv;        /* bf16 [3C, C]: rows 0..C-1 = W_q, C..2C-1 = W_k, 2C..3C-1 = W_v */
+    const float* b_qkv;       /* [3C] */
+    const float* g_q;         /* [C] RMSNorm gain of q (norm over all C) */
+    const float* g_k;         /* [C] */
+    const void* W_o;          /* bf16 [C, C] */
+    const float* b_o;         /* [C] */
+    const float* mod_table;   /* [6, C]: shift1, scale1, gate1, shift2, scale2, gate2 (added to e0) */
+    const float* ln3_gamma;   /* [C] affine LayerNorm before the cross-attention */
+    const float* ln3_beta;    /* [C] */
+    const void* W_cq;         /* bf16 [C, C] */
+    const float* b_cq;        /* [C] */
+    const float* g_cq;        /* [C] */
+    const void* W_ck;         /* bf16 [C, C]  (used by sdv2_text_kv_prepare only) */
+    const float* b_ck;
+    const float* g_ck;
+    const void* W_cv;         /* bf16 [C, C]  (used by sdv2_text_kv_prepare only) */
+    const float* b_cv;
+    const void* W_co;         /* bf16 [C, C] */
+    const float* b_co;
+    const void* W_1;          /* bf16 [F, C] */
+    const float* b_1;         /* [F] */
+    const void* W_2;          /* bf16 [C, F] */
+    const float* b_2;         /* [C] */
+} sdv2_block_weights;
+
+/* Whole-model parameters. */
+typedef struct sdv2_model_weights {
+    uint32_t struct_size;
+    uint32_t reserved;
+    const sdv2_block_weights* blocks;   /* host array [n_layers] */
+    const void* W_t1;         /* bf16 [C, t_dim] */
+    const float* b_t1;        /* [C] */
+    const void* W_t2;         /* bf16 [C, C] */
+    const float* b_t2;        /* [C] */
+    const void* W_mod;        /* bf16 [6C, C] */
+    const float* b_mod;       /* [6C] */
+} sdv2_model_weights;
+
+/* What one stream contributes to a batched call. */
+typedef struct sdv2_chunk_desc {
+    int32_t stream_id;        /* which cache stream; distinct within one call */
+    int32_t frame_pos0;       /* RoPE frame index of the chunk's first frame (caller's policy) */
+    int32_t n_frames;         /* frames in the chunk; the same for every stream of a call */
+    int32_t advance;          /* 1: a new chunk (appends, evicts); 0: a further denoising step of the
+                                 chunk appended last (overwrites its K/V in place) */
+} sdv2_chunk_desc;
+
+/* Host-side view of one (layer, stream) cache; compared bit for bit in the tests. */
+typedef struct sdv2_cache_state {
+    int64_t total;            /* tokens ever appended */
+    int64_t evicted;          /* tokens that have left the window */
+    int32_t sink_fill;
+    int32_t win_fill;
+    int32_t oldest_slot;      /* physical slot of the oldest window token, -1 if the window is empty */
+    int32_t next_slot;        /* physical slot the next token will take */
+} sdv2_cache_state;
+
+typedef struct sdv2_kv_cache sdv2_kv_cache;   /* opaque host handle */
+
+const char* sdv2_last_error(void);
+int32_t sdv2_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Rolling KV cache (abstract; Section 1; Appendix D rolling-KV-cache figure).
+ *
+ * Token g (0-based count of tokens ever appended to a stream's layer) lives in physical slot
+ *     slot(g) = g                      if g < S        (sink: written once, never evicted)
+ *               S + (g - S) mod W      otherwise       (ring: a token leaves when a later one
+ *                                                       lands on its slot, i.e. first in first out)
+ * Resident tokens always occupy the slot prefix [0, min(total, S + W)).
+ *
+ * Device layout per (layer, stream), cap = S + W rounded up to a multiple of 64:
+ *     K    bf16 [n_heads][cap][128]      (post-RMSNorm, post-RoPE keys)
+ *     V^T  bf16 [n_heads][128][cap]      (values, slot index contiguous)
+ *     ids  int64 [cap]                   (token id held by each slot, written by the append kernel;
+ *                                         meaningful only for slots < min(total, S + W))
+ * ------------------------------------------------------------------------------------------------ */
+
+/* Bytes of device storage the caller must provide for the whole cache (0 on bad cfg). */
+size_t sdv2_kv_cache_bytes(const sdv2_cache_cfg* cfg);
+
+/* Create a handle over caller-owned storage `dev_storage` (256-byte aligned, `bytes` long, must
+ * outlive the handle).  All streams start empty.  Nothing is launched; storage is not cleared.
+ * Errors: null pointers, S < 0, W <= 0, S or W not a multiple of tokens_per_frame, bytes too small. */
+int32_t sdv2_kv_cache_init(const sdv2_cache_cfg* cfg, void* dev_storage, size_t bytes, sdv2_kv_cache** out);
+
+/* Free the host handle only. */
+int32_t sdv2_kv_cache_destroy(sdv2_kv_cache* cache);
+
+/* Forget one stream (all layers): total = 0.  Host-only. */
+int32_t sdv2_kv_cache_reset(sdv2_kv_cache* cache, int32_t stream_id);
+
+/* Append n_tokens final keys/values (dev, bf16 [n_tokens, C], already normalised and rotated).
+ * advance = 1: the tokens get ids [total, total + n_tokens), total grows, the oldest window tokens
+ *              that no longer fit are evicted (overwritten).
+ * advance = 0: rewrites the values of the most recent append in place; needs the same n_tokens
+ *              (else SDV2_BAD_STATE).
+ * Errors: n_tokens <= 0, > W, or not a multiple of tokens_per_frame; bad layer / stream.
+ * sdv2_dit_block_forward performs the identical state transition with its fused kernel. */
+int32_t sdv2_kv_cache_append_evict(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id,
+                                   const void* k_dev, const void* v_dev, int32_t n_tokens,
+                                   int32_t advance, void* hip_stream);
+
+/* Host-side state and slot map (no device access, no synchronisation).
+ * slot_map_out: host int64 [S + W]; token id per slot, -1 where nothing is resident. */
+int32_t sdv2_kv_cache_state(const sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, sdv2_cache_state* out);
+int32_t sdv2_kv_cache_slot_map(const sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int64_t* slot_map_out);
+
+/* Device addresses of one (layer, stream) cache and its padded capacity (for read-back in tests). */
+int32_t sdv2_kv_cache_device_ptrs(const sdv2_kv_cache* cache, int32_t layer, int32_t stream_id,
+                                  void** k_dev, void** vt_dev, int64_t** ids_dev, int32_t* cap);
+
+/* ------------------------------------------------------------------------------------------------
+ * Text keys/values of the cross-attention (per prompt and layer; off the per-chunk path: prompt
+ * changes are events, Section 1 "Vision quality objectives").
+ *   K_t = RMSNorm(ctx W_ck^T + b_ck) g_ck,   V_t = ctx W_cv^T + b_cv
+ * Output layout matches the cache: K_t bf16 [n_heads][cap_t][128], V_t^T bf16 [n_heads][128][cap_t],
+ * cap_t = text_len rounded up to 64.  sdv2_text_kv_bytes gives the bytes of EACH of the two buffers.
+ * ctx_dev: bf16 [text_len, C].  Workspace: sdv2_text_kv_workspace_bytes.
+ * ------------------------------------------------------------------------------------------------ */
+size_t sdv2_text_kv_bytes(const sdv2_model_cfg* cfg);
+size_t sdv2_text_kv_workspace_bytes(const sdv2_model_cfg* cfg);
+int32_t sdv2_text_kv_prepare(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, const void* ctx_dev,
+                             void* kt_dev, void* vtt_dev, void* workspace_dev, size_t workspace_bytes,
+                             void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Timestep conditioning, once per denoising step:
+ *   tvec = W_t2 SiLU(W_t1 emb(t) + b_t1) + b_t2,  emb(t) = [cos(t w_j) | sin(t w_j)], w_j = base^(-j/(t_dim/2))
+ *   e0   = W_mod SiLU(tvec) + b_mod            -> dev fp32 [B, 6, C]
+ * Exactly one of timesteps_host (host float [B]) and tvec_dev (dev fp32 [B, C]) is non-null; with
+ * tvec_dev the first line is skipped.  Workspace: sdv2_conditioning_workspace_bytes(cfg, B).
+ * ------------------------------------------------------------------------------------------------ */
+size_t sdv2_conditioning_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B);
+int32_t sdv2_conditioning(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, int32_t B,
+                          const float* timesteps_host, const float* tvec_dev, float* e0_dev,
+                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * One causal DiT block on one chunk of B streams (the per-layer work costed in Appendix B):
+ *   (shift1, scale1, gate1, shift2, scale2, gate2) = mod_table + e0[b]
+ *   h = LN(x)(1 + scale1) + shift1;  q, k, v = h W_qkv^T + b_qkv
+ *   q = RoPE3D(RMSNorm(q) g_q), k = RoPE3D(RMSNorm(k) g_k) at (frame_pos0 + i / P, row, col)
+ *   append k, v to the stream's cache (evicting), then  o = softmax(q K^T / sqrt(128)) V over every
+ *   resident token, the chunk's own included;  x += gate1 * (o W_o^T + b_o)
+ *   x += softmax(RMSNorm(LN3(x) W_cq^T + b_cq) g_cq K_t^T / sqrt(128)) V_t W_co^T + b_co
+ *   x += gate2 * (GELU_tanh((LN(x)(1 + scale2) + shift2) W_1^T + b_1) W_2^T + b_2)
+ * x_dev:   fp32 [B, L, C], in place, L = n_frames * tokens_per_frame.
+ * e0_dev:  fp32 [B, 6, C].   kt_dev / vtt_dev: this layer's text K/V for each stream of the call, as
+ * arrays of B dev pointers held on the host (streams may have different prompts).
+ * chunks:  host array [B].  Mutates x and, for each listed stream, this layer's cache and host state.
+ * Errors: B < 1 or > SDV2_MAX_BATCH, repeated stream_id, L > W, unequal n_frames, advance = 0
+ * without a matching append, workspace smaller than sdv2_block_workspace_bytes(cfg, B, L).
+ * ------------------------------------------------------------------------------------------------ */
+size_t sdv2_block_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L);
+int32_t sdv2_dit_block_forward(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_kv_cache* cache,
+                               int32_t layer, float* x_dev, const float* e0_dev,
+                               const void* const* kt_dev, const void* const* vtt_dev,
+                               const sdv2_chunk_desc* chunks, int32_t B,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * One denoising step of a chunk (Section 5.1: 1-4 steps per chunk): conditioning, then blocks
+ * 0..n_layers-1 in order, each on its own cache.  Hidden state in, hidden state out.
+ * timesteps_host / tvec_dev: as in sdv2_conditioning.
+ * kt_dev / vtt_dev: host arrays [n_layers * B] of dev pointers, index layer * B + b.
+ * Workspace: sdv2_denoise_workspace_bytes(cfg, B, L).
+ * ------------------------------------------------------------------------------------------------ */
+size_t sdv2_denoise_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L);
+int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache,
+                          float* x_dev, const float* timesteps_host, const float* tvec_dev,
+                          const void* const* kt_dev, const void* const* vtt_dev,
+                          const sdv2_chunk_desc* chunks, int32_t B,
+                          void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * The two dense kernels on their own (used by the per-kernel parity tests and the benchmark).
+ *
+ * sdv2_gemm_bf16: out = epilogue(a W^T + bias).  a: bf16 [M, K]; w: bf16 [N, K]; bias fp32 [N] or NULL.
+ *   epilogue 0: out bf16 [M, N] = acc + bias
+ *            1: out bf16 [M, N] = GELU_tanh(acc + bias)
+ *            2: out fp32 [M, N] += gate[row / rows_per_gate][n] * (acc + bias), gate = gate_a[n] +
+ *               gate_b[(row / rows_per_gate) * gate_b_stride + n]
+ *            3: out fp32 [M, N] += acc + bias
+ *   K multiple of 64, N multiple of 128 (else SDV2_INVALID_ARG).
+ *
+ * sdv2_attention_bf16: o[b] = softmax(q[b] K[b]^T / sqrt(128)) V[b] over kv_len[b] slots.
+ *   q: bf16 [B, L, C]; k[b]: bf16 [H][cap][128]; vt[b]: bf16 [H][128][cap] (cap multiple of 64,
+ *   >= kv_len[b] > 0); o: bf16 [B, L, C].  workspace: sdv2_attention_workspace_bytes(B, L, C, max kv_len).
+ * ------------------------------------------------------------------------------------------------ */
+int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_dev, void* out_dev,
+                       int32_t M, int32_t N, int32_t K, int32_t epilogue,
+                       const float* gate_a_dev, const float* gate_b_dev, int32_t gate_b_stride,
+                       int32_t rows_per_gate, void* hip_stream);
+size_t sdv2_attention_workspace_bytes(int32_t B, int32_t L, int32_t C, int32_t max_kv_len);
+int32_t sdv2_attention_bf16(const void* q_dev, const void* const* k_dev, const void* const* vt_dev,
+                            const int32_t* kv_len_host, const int32_t* cap_host, void* o_dev,
+                            int32_t B, int32_t L, int32_t n_heads,
+                            void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Per-launch timing for the benchmark (not part of the streaming path).  Between sdv2_prof_begin and
+ * sdv2_prof_end every kernel launch site of sdv2_dit_block_forward / sdv2_denoise_step is bracketed by
+ * a pair of HIP events on the caller's stream, up to max_samples launches.  sdv2_prof_end waits for
+ * the recorded events (the only call of the library that blocks), writes one (tag, milliseconds) per
+ * launch in launch order into the host arrays and destroys the events.  Not thread safe.
+ * ------------------------------------------------------------------------------------------------ */
+enum sdv2_launch_tag {
+    SDV2_TAG_ADALN1 = 0, SDV2_TAG_QKV = 1, SDV2_TAG_ROPE_APPEND = 2, SDV2_TAG_SELF_ATTN = 3,
+    SDV2_TAG_OUT_PROJ = 4, SDV2_TAG_LN3 = 5, SDV2_TAG_CROSS_Q = 6, SDV2_TAG_CROSS_Q_NORM = 7,
+    SDV2_TAG_CROSS_ATTN = 8, SDV2_TAG_CROSS_OUT = 9, SDV2_TAG_ADALN2 = 10, SDV2_TAG_FFN1 = 11,
+    SDV2_TAG_FFN2 = 12, SDV2_TAG_COUNT = 13
+};
+int32_t sdv2_prof_begin(int32_t max_samples);
+int32_t sdv2_prof_end(int32_t* tags_out, float* ms_out, int32_t capacity, int32_t* n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDV2_H */

@@ -6,4 +6,4 @@ Importing the package does not load the library; the first call does, and it
 raises if the library has not been built.
 """
 
-__all__ = ["workloads", "cost_model", "binding"]
+__all__ = ["workloads", "cost_model", "binding", "runner"]

@@ -1,0 +1,814 @@
+// Host side of libsdv2: argument validation, ring bookkeeping, workspace carving and the launch
+// sequence of the block.  See include/sdv2.h for the contract of every exported call.
+#include "common.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/sdv2.h"
+
+using namespace sdv2;
+
+// ------------------------------------------------------------------------------------------ errors
+namespace {
+
+thread_local std::string g_last_error;
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+int32_t hip_fail(hipError_t e, const char* what) {
+    return fail(SDV2_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(expr, what)                           \
+    do {                                              \
+        hipError_t e__ = (expr);                      \
+        if (e__ != hipSuccess) return hip_fail(e__, what); \
+    } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Optional per-launch timing with HIP events (sdv2_prof_begin / sdv2_prof_end).
+struct Profiler {
+    bool on = false;
+    int n = 0;
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int> tag;
+};
+Profiler g_prof;
+
+template <typename F>
+hipError_t timed(int tag, hipStream_t s, F&& launch) {
+    if (!g_prof.on || g_prof.n >= (int)g_prof.start.size()) return launch();
+    const int i = g_prof.n++;
+    g_prof.tag[i] = tag;
+    hipError_t e = hipEventRecord(g_prof.start[i], s);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    return hipEventRecord(g_prof.stop[i], s);
+}
+
+bool model_cfg_ok(const sdv2_model_cfg* c, const char** why) {
+    *why = nullptr;
+    if (!c) *why = "cfg is null";
+    else if (c->struct_size != sizeof(sdv2_model_cfg)) *why = "cfg.struct_size mismatch";
+    else if (c->n_heads <= 0 || c->C != c->n_heads * SDV2_HEAD_DIM) *why = "C must equal n_heads * 128";
+    else if (c->C > 8192) *why = "C > 8192";
+    else if (c->ffn_dim <= 0 || c->ffn_dim % 128) *why = "ffn_dim must be a positive multiple of 128";
+    else if (c->grid_h <= 0 || c->grid_w <= 0) *why = "grid must be positive";
+    else if (c->text_len <= 0) *why = "text_len must be positive";
+    else if (c->n_layers <= 0) *why = "n_layers must be positive";
+    else if (c->t_dim <= 0 || c->t_dim % 8) *why = "t_dim must be a positive multiple of 8";
+    else if (!(c->eps > 0.0f) || !(c->rope_base > 1.0f)) *why = "eps / rope_base out of range";
+    return *why == nullptr;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------ cache handle
+struct sdv2_kv_cache {
+    sdv2_cache_cfg cfg;
+    int cap;                       // S + W rounded up to 64
+    unsigned char* base;
+    size_t k_bytes, ids_bytes, unit_bytes;   // per (layer, stream)
+    std::vector<int64_t> total;    // [layer * n_streams + stream]
+    std::vector<int32_t> last_n;   // size of the most recent advancing append (0: none)
+};
+
+namespace {
+
+bool cache_cfg_ok(const sdv2_cache_cfg* c, const char** why) {
+    *why = nullptr;
+    if (!c) *why = "cfg is null";
+    else if (c->struct_size != sizeof(sdv2_cache_cfg)) *why = "cfg.struct_size mismatch";
+    else if (c->n_layers <= 0 || c->n_streams <= 0 || c->n_heads <= 0) *why = "n_layers, n_streams, n_heads must be positive";
+    else if (c->tokens_per_frame <= 0) *why = "tokens_per_frame must be positive";
+    else if (c->sink_tokens < 0) *why = "sink_tokens < 0";
+    else if (c->window_tokens <= 0) *why = "window_tokens <= 0";
+    else if (c->sink_tokens % c->tokens_per_frame || c->window_tokens % c->tokens_per_frame)
+        *why = "sink_tokens and window_tokens must be whole frames";
+    else if ((int64_t)c->sink_tokens + c->window_tokens > (1 << 30)) *why = "cache too large";
+    return *why == nullptr;
+}
+
+void cache_geometry(const sdv2_cache_cfg* c, int* cap, size_t* k_bytes, size_t* ids_bytes, size_t* unit) {
+    *cap = (int)align_up((size_t)c->sink_tokens + c->window_tokens, 64);
+    *k_bytes = (size_t)c->n_heads * *cap * SDV2_HEAD_DIM * sizeof(bf16);
+    *ids_bytes = (size_t)*cap * sizeof(int64_t);
+    *unit = align_up(2 * *k_bytes + *ids_bytes, 256);
+}
+
+int slot_of_host(int64_t g, int S, int W) { return g < S ? (int)g : S + (int)((g - S) % W); }
+
+int32_t check_layer_stream(const sdv2_kv_cache* c, int32_t layer, int32_t stream) {
+    if (!c) return fail(SDV2_INVALID_ARG, "cache handle is null");
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(SDV2_INVALID_ARG, "layer %d out of range", layer);
+    if (stream < 0 || stream >= c->cfg.n_streams) return fail(SDV2_INVALID_ARG, "stream %d out of range", stream);
+    return SDV2_OK;
+}
+
+AppendStream append_stream(const sdv2_kv_cache* c, int layer, int stream, int64_t g0, int frame_pos0) {
+    unsigned char* u = c->base + ((size_t)layer * c->cfg.n_streams + stream) * c->unit_bytes;
+    AppendStream s;
+    s.k_cache = reinterpret_cast<bf16*>(u);
+    s.vt_cache = reinterpret_cast<bf16*>(u + c->k_bytes);
+    s.ids = reinterpret_cast<long long*>(u + 2 * c->k_bytes);
+    s.g0 = g0;
+    s.frame_pos0 = frame_pos0;
+    s.cap = c->cap;
+    return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sdv2_last_error(void) { return g_last_error.c_str(); }
+int32_t sdv2_version(void) { return 1; }
+
+size_t sdv2_kv_cache_bytes(const sdv2_cache_cfg* cfg) {
+    const char* why;
+    if (!cache_cfg_ok(cfg, &why)) {
+        fail(SDV2_INVALID_ARG, "%s", why);
+        return 0;
+    }
+    int cap;
+    size_t kb, ib, unit;
+    cache_geometry(cfg, &cap, &kb, &ib, &unit);
+    return unit * cfg->n_layers * cfg->n_streams;
+}
+
+int32_t sdv2_kv_cache_init(const sdv2_cache_cfg* cfg, void* dev_storage, size_t bytes, sdv2_kv_cache** out) {
+    const char* why;
+    if (!cache_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!dev_storage || !out) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (reinterpret_cast<uintptr_t>(dev_storage) % 256) return fail(SDV2_INVALID_ARG, "storage must be 256-byte aligned");
+    const size_t need = sdv2_kv_cache_bytes(cfg);
+    if (bytes < need) return fail(SDV2_INVALID_ARG, "storage too small: %zu < %zu", bytes, need);
+    sdv2_kv_cache* c = new (std::nothrow) sdv2_kv_cache;
+    if (!c) return fail(SDV2_INVALID_ARG, "out of host memory");
+    c->cfg = *cfg;
+    cache_geometry(cfg, &c->cap, &c->k_bytes, &c->ids_bytes, &c->unit_bytes);
+    c->base = static_cast<unsigned char*>(dev_storage);
+    c->total.assign((size_t)cfg->n_layers * cfg->n_streams, 0);
+    c->last_n.assign((size_t)cfg->n_layers * cfg->n_streams, 0);
+    *out = c;
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_destroy(sdv2_kv_cache* cache) {
+    delete cache;
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_reset(sdv2_kv_cache* cache, int32_t stream_id) {
+    int32_t rc = check_layer_stream(cache, 0, stream_id);
+    if (rc) return rc;
+    for (int l = 0; l < cache->cfg.n_layers; ++l) {
+        cache->total[(size_t)l * cache->cfg.n_streams + stream_id] = 0;
+        cache->last_n[(size_t)l * cache->cfg.n_streams + stream_id] = 0;
+    }
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_state(const sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, sdv2_cache_state* out) {
+    int32_t rc = check_layer_stream(cache, layer, stream_id);
+    if (rc) return rc;
+    if (!out) return fail(SDV2_INVALID_ARG, "out is null");
+    const int S = cache->cfg.sink_tokens, W = cache->cfg.window_tokens;
+    const int64_t total = cache->total[(size_t)layer * cache->cfg.n_streams + stream_id];
+    out->total = total;
+    out->sink_fill = (int32_t)(total < S ? total : S);
+    const int64_t in_win = total > S ? total - S : 0;
+    out->win_fill = (int32_t)(in_win < W ? in_win : W);
+    out->evicted = in_win > W ? in_win - W : 0;
+    out->oldest_slot = out->win_fill ? slot_of_host(total - out->win_fill, S, W) : -1;
+    out->next_slot = slot_of_host(total, S, W);
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_slot_map(const sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int64_t* slot_map_out) {
+    int32_t rc = check_layer_stream(cache, layer, stream_id);
+    if (rc) return rc;
+    if (!slot_map_out) return fail(SDV2_INVALID_ARG, "slot_map_out is null");
+    const int S = cache->cfg.sink_tokens, W = cache->cfg.window_tokens;
+    const int64_t total = cache->total[(size_t)layer * cache->cfg.n_streams + stream_id];
+    for (int i = 0; i < S + W; ++i) slot_map_out[i] = -1;
+    const int64_t sink_end = total < S ? total : S;
+    for (int64_t g = 0; g < sink_end; ++g) slot_map_out[g] = g;
+    int64_t first = total - W;
+    if (first < S) first = S;
+    for (int64_t g = first; g < total; ++g) slot_map_out[slot_of_host(g, S, W)] = g;
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_device_ptrs(const sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, void** k_dev,
+                                  void** vt_dev, int64_t** ids_dev, int32_t* cap) {
+    int32_t rc = check_layer_stream(cache, layer, stream_id);
+    if (rc) return rc;
+    AppendStream s = append_stream(cache, layer, stream_id, 0, 0);
+    if (k_dev) *k_dev = s.k_cache;
+    if (vt_dev) *vt_dev = s.vt_cache;
+    if (ids_dev) *ids_dev = reinterpret_cast<int64_t*>(s.ids);
+    if (cap) *cap = cache->cap;
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_append_evict(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, const void* k_dev,
+                                   const void* v_dev, int32_t n_tokens, int32_t advance, void* hip_stream) {
+    int32_t rc = check_layer_stream(cache, layer, stream_id);
+    if (rc) return rc;
+    if (!k_dev || !v_dev) return fail(SDV2_INVALID_ARG, "k/v is null");
+    const sdv2_cache_cfg& cf = cache->cfg;
+    if (n_tokens <= 0 || n_tokens > cf.window_tokens || n_tokens % cf.tokens_per_frame)
+        return fail(SDV2_INVALID_ARG, "n_tokens %d must be whole frames, positive and at most the window", n_tokens);
+    const size_t idx = (size_t)layer * cf.n_streams + stream_id;
+    if (!advance && cache->last_n[idx] != n_tokens)
+        return fail(SDV2_BAD_STATE, "advance = 0 needs a previous append of %d tokens (last was %d)", n_tokens,
+                    cache->last_n[idx]);
+    const int64_t old_total = cache->total[idx];
+    const int32_t old_last = cache->last_n[idx];
+    if (advance) {
+        cache->total[idx] += n_tokens;
+        cache->last_n[idx] = n_tokens;
+    }
+    PlainAppendArgs a;
+    a.k = static_cast<const bf16*>(k_dev);
+    a.v = static_cast<const bf16*>(v_dev);
+    a.n = n_tokens;
+    a.C = cf.n_heads * SDV2_HEAD_DIM;
+    a.H = cf.n_heads;
+    a.S = cf.sink_tokens;
+    a.W = cf.window_tokens;
+    a.st = append_stream(cache, layer, stream_id, cache->total[idx] - n_tokens, 0);
+    hipError_t e = launch_plain_append(a, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        cache->total[idx] = old_total;
+        cache->last_n[idx] = old_last;
+        return hip_fail(e, "append kernel");
+    }
+    return SDV2_OK;
+}
+
+// ------------------------------------------------------------------------------------------ dense helpers
+int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_dev, void* out_dev, int32_t M,
+                       int32_t N, int32_t K, int32_t epilogue, const float* gate_a_dev, const float* gate_b_dev,
+                       int32_t gate_b_stride, int32_t rows_per_gate, void* hip_stream) {
+    if (!a_dev || !w_dev || !out_dev) return fail(SDV2_INVALID_ARG, "null operand");
+    if (M <= 0 || N <= 0 || K <= 0) return fail(SDV2_INVALID_ARG, "M, N, K must be positive");
+    if (K % 64) return fail(SDV2_INVALID_ARG, "K = %d must be a multiple of 64", K);
+    if (N % 128) return fail(SDV2_INVALID_ARG, "N = %d must be a multiple of 128", N);
+    if (epilogue < 0 || epilogue > 3) return fail(SDV2_INVALID_ARG, "epilogue %d unknown", epilogue);
+    if (epilogue == kEpiGatedResidual && (!gate_a_dev || !gate_b_dev || rows_per_gate <= 0))
+        return fail(SDV2_INVALID_ARG, "gated epilogue needs gate_a, gate_b and rows_per_gate > 0");
+    GemmArgs g;
+    g.a = static_cast<const bf16*>(a_dev);
+    g.w = static_cast<const bf16*>(w_dev);
+    g.bias = bias_dev;
+    g.out = out_dev;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.epilogue = epilogue;
+    g.gate_a = gate_a_dev;
+    g.gate_b = gate_b_dev;
+    g.gate_b_stride = gate_b_stride;
+    g.rows_per_gate = rows_per_gate > 0 ? rows_per_gate : 1;
+    HIP_TRY(launch_gemm(g, static_cast<hipStream_t>(hip_stream)), "gemm kernel");
+    return SDV2_OK;
+}
+
+size_t sdv2_attention_workspace_bytes(int32_t B, int32_t L, int32_t C, int32_t max_kv_len) {
+    if (B <= 0 || L <= 0 || C <= 0 || C % SDV2_HEAD_DIM || max_kv_len <= 0) return 0;
+    return align_up(attention_workspace_bytes(B, L, C, max_kv_len), 256);
+}
+
+int32_t sdv2_attention_bf16(const void* q_dev, const void* const* k_dev, const void* const* vt_dev,
+                            const int32_t* kv_len_host, const int32_t* cap_host, void* o_dev, int32_t B, int32_t L,
+                            int32_t n_heads, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    if (!q_dev || !k_dev || !vt_dev || !kv_len_host || !cap_host || !o_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (B <= 0 || B > SDV2_MAX_BATCH || L <= 0 || n_heads <= 0) return fail(SDV2_INVALID_ARG, "bad B, L or n_heads");
+    AttnArgs a;
+    memset(&a, 0, sizeof(a));
+    int max_kv = 0;
+    for (int b = 0; b < B; ++b) {
+        if (!k_dev[b] || !vt_dev[b]) return fail(SDV2_INVALID_ARG, "null K/V of stream %d", b);
+        if (kv_len_host[b] <= 0 || cap_host[b] % 64 || cap_host[b] < kv_len_host[b])
+            return fail(SDV2_INVALID_ARG, "stream %d: need 0 < kv_len <= cap, cap multiple of 64", b);
+        a.k[b] = static_cast<const bf16*>(k_dev[b]);
+        a.vt[b] = static_cast<const bf16*>(vt_dev[b]);
+        a.kv_len[b] = kv_len_host[b];
+        a.cap[b] = cap_host[b];
+        if (kv_len_host[b] > max_kv) max_kv = kv_len_host[b];
+    }
+    const int C = n_heads * SDV2_HEAD_DIM;
+    a.splits = attention_plan_splits(B, L, n_heads, max_kv);
+    const size_t need = align_up(attention_workspace_bytes(B, L, C, max_kv), 256);
+    if (need > 0 && (!workspace_dev || workspace_bytes < need))
+        return fail(SDV2_WORKSPACE_TOO_SMALL, "attention workspace %zu < %zu", workspace_bytes, need);
+    a.q = static_cast<const bf16*>(q_dev);
+    a.o = static_cast<bf16*>(o_dev);
+    a.B = B;
+    a.L = L;
+    a.H = n_heads;
+    a.part_o = static_cast<float*>(workspace_dev);
+    a.part_ml = a.part_o ? a.part_o + (size_t)a.splits * B * L * C : nullptr;
+    HIP_TRY(launch_attention(a, static_cast<hipStream_t>(hip_stream)), "attention kernel");
+    return SDV2_OK;
+}
+
+// ------------------------------------------------------------------------------------------ text K/V
+size_t sdv2_text_kv_bytes(const sdv2_model_cfg* cfg) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) {
+        fail(SDV2_INVALID_ARG, "%s", why);
+        return 0;
+    }
+    return align_up((size_t)cfg->text_len, 64) * cfg->C * sizeof(bf16);
+}
+
+size_t sdv2_text_kv_workspace_bytes(const sdv2_model_cfg* cfg) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) {
+        fail(SDV2_INVALID_ARG, "%s", why);
+        return 0;
+    }
+    return 2 * align_up((size_t)cfg->text_len * cfg->C * sizeof(bf16), 256);
+}
+
+int32_t sdv2_text_kv_prepare(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, const void* ctx_dev,
+                             void* kt_dev, void* vtt_dev, void* workspace_dev, size_t workspace_bytes,
+                             void* hip_stream) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!w || w->struct_size != sizeof(sdv2_block_weights)) return fail(SDV2_INVALID_ARG, "bad block weights");
+    if (!w->W_ck || !w->b_ck || !w->g_ck || !w->W_cv || !w->b_cv) return fail(SDV2_INVALID_ARG, "text K/V weights missing");
+    if (!ctx_dev || !kt_dev || !vtt_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    const size_t need = sdv2_text_kv_workspace_bytes(cfg);
+    if (workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int C = cfg->C, Lt = cfg->text_len;
+    bf16* krows = static_cast<bf16*>(workspace_dev);
+    bf16* vrows = reinterpret_cast<bf16*>(static_cast<unsigned char*>(workspace_dev) + need / 2);
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.a = static_cast<const bf16*>(ctx_dev);
+    g.M = Lt;
+    g.N = C;
+    g.K = C;
+    g.epilogue = kEpiBias;
+    g.rows_per_gate = 1;
+    g.w = static_cast<const bf16*>(w->W_ck);
+    g.bias = w->b_ck;
+    g.out = krows;
+    HIP_TRY(launch_gemm(g, s), "text K gemm");
+    HIP_TRY(launch_rmsnorm_inplace(krows, w->g_ck, Lt, C, C, cfg->eps, s), "text K norm");
+    g.w = static_cast<const bf16*>(w->W_cv);
+    g.bias = w->b_cv;
+    g.out = vrows;
+    HIP_TRY(launch_gemm(g, s), "text V gemm");
+    HIP_TRY(launch_text_relayout(krows, vrows, static_cast<bf16*>(kt_dev), static_cast<bf16*>(vtt_dev), Lt, C,
+                                 cfg->n_heads, (int)align_up((size_t)Lt, 64), s),
+            "text relayout");
+    return SDV2_OK;
+}
+
+// ------------------------------------------------------------------------------------------ conditioning
+size_t sdv2_conditioning_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why) || B <= 0 || B > SDV2_MAX_BATCH) {
+        fail(SDV2_INVALID_ARG, "bad cfg or B");
+        return 0;
+    }
+    return align_up((size_t)B * cfg->t_dim * 4, 256) + 2 * align_up((size_t)B * cfg->C * 4, 256);
+}
+
+int32_t sdv2_conditioning(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, int32_t B,
+                          const float* timesteps_host, const float* tvec_dev, float* e0_dev, void* workspace_dev,
+                          size_t workspace_bytes, void* hip_stream) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (B <= 0 || B > SDV2_MAX_BATCH) return fail(SDV2_INVALID_ARG, "B = %d out of range", B);
+    if (!mw || mw->struct_size != sizeof(sdv2_model_weights)) return fail(SDV2_INVALID_ARG, "bad model weights");
+    if ((timesteps_host == nullptr) == (tvec_dev == nullptr))
+        return fail(SDV2_INVALID_ARG, "give exactly one of timesteps_host and tvec_dev");
+    if (!e0_dev || !mw->W_mod || !mw->b_mod) return fail(SDV2_INVALID_ARG, "null pointer");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int C = cfg->C;
+    const float* tvec = tvec_dev;
+    if (timesteps_host) {
+        if (!mw->W_t1 || !mw->b_t1 || !mw->W_t2 || !mw->b_t2) return fail(SDV2_INVALID_ARG, "timestep MLP weights missing");
+        const size_t need = sdv2_conditioning_workspace_bytes(cfg, B);
+        if (!workspace_dev || workspace_bytes < need)
+            return fail(SDV2_WORKSPACE_TOO_SMALL, "conditioning workspace %zu < %zu", workspace_bytes, need);
+        unsigned char* p = static_cast<unsigned char*>(workspace_dev);
+        float* emb = reinterpret_cast<float*>(p);
+        p += align_up((size_t)B * cfg->t_dim * 4, 256);
+        float* a1 = reinterpret_cast<float*>(p);
+        p += align_up((size_t)B * C * 4, 256);
+        float* tv = reinterpret_cast<float*>(p);
+        HIP_TRY(launch_timestep_embedding(timesteps_host, emb, B, cfg->t_dim, (double)cfg->rope_base, s), "timestep embedding");
+        HIP_TRY(launch_gemv(emb, static_cast<const bf16*>(mw->W_t1), mw->b_t1, a1, B, C, cfg->t_dim, 0, s), "timestep MLP 1");
+        HIP_TRY(launch_gemv(a1, static_cast<const bf16*>(mw->W_t2), mw->b_t2, tv, B, C, C, 1, s), "timestep MLP 2");
+        tvec = tv;
+    }
+    HIP_TRY(launch_gemv(tvec, static_cast<const bf16*>(mw->W_mod), mw->b_mod, e0_dev, B, 6 * C, C, 1, s), "modulation projection");
+    return SDV2_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------ the block
+namespace {
+
+struct BlockWorkspace {
+    bf16* h;        // [rows, C]
+    bf16* qkv;      // [rows, 3C]
+    bf16* q;        // [rows, C]
+    bf16* o;        // [rows, C]
+    bf16* u;        // [rows, F]
+    float* attn;    // split-KV partials
+    size_t attn_bytes;
+    size_t total;
+};
+
+BlockWorkspace carve_block(const sdv2_model_cfg* cfg, int B, int L, int max_kv, unsigned char* base) {
+    const size_t rows = (size_t)B * L;
+    const size_t C = cfg->C, F = cfg->ffn_dim;
+    BlockWorkspace w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        unsigned char* p = base ? base + off : nullptr;
+        off += align_up(bytes, 256);
+        return p;
+    };
+    w.h = reinterpret_cast<bf16*>(take(rows * C * 2));
+    w.qkv = reinterpret_cast<bf16*>(take(rows * 3 * C * 2));
+    w.q = reinterpret_cast<bf16*>(take(rows * C * 2));
+    w.o = reinterpret_cast<bf16*>(take(rows * C * 2));
+    w.u = reinterpret_cast<bf16*>(take(rows * F * 2));
+    const size_t a1 = attention_workspace_bytes(B, L, (int)C, max_kv);
+    const size_t a2 = attention_workspace_bytes(B, L, (int)C, cfg->text_len);
+    w.attn_bytes = a1 > a2 ? a1 : a2;
+    w.attn = reinterpret_cast<float*>(take(w.attn_bytes));
+    w.total = off;
+    return w;
+}
+
+// Everything that can be rejected without touching state.  Fills per-stream L and returns it.
+int32_t validate_block_call(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, const sdv2_kv_cache* cache,
+                            int32_t layer, const sdv2_chunk_desc* chunks, int32_t B, int* L_out) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!w || w->struct_size != sizeof(sdv2_block_weights)) return fail(SDV2_INVALID_ARG, "bad block weights (layer %d)", layer);
+    const void* need[] = {w->W_qkv, w->b_qkv, w->g_q, w->g_k, w->W_o, w->b_o, w->mod_table, w->ln3_gamma, w->ln3_beta,
+                          w->W_cq, w->b_cq, w->g_cq, w->W_co, w->b_co, w->W_1, w->b_1, w->W_2, w->b_2};
+    for (const void* p : need)
+        if (!p) return fail(SDV2_INVALID_ARG, "a weight pointer of layer %d is null", layer);
+    if (!cache) return fail(SDV2_INVALID_ARG, "cache handle is null");
+    if (layer < 0 || layer >= cache->cfg.n_layers) return fail(SDV2_INVALID_ARG, "layer %d out of range", layer);
+    if (cache->cfg.n_heads != cfg->n_heads || cache->cfg.tokens_per_frame != cfg->grid_h * cfg->grid_w)
+        return fail(SDV2_INVALID_ARG, "cache and model shapes disagree");
+    if (B < 1 || B > SDV2_MAX_BATCH) return fail(SDV2_INVALID_ARG, "B = %d out of range", B);
+    if (!chunks) return fail(SDV2_INVALID_ARG, "chunks is null");
+    const int P = cfg->grid_h * cfg->grid_w;
+    for (int b = 0; b < B; ++b) {
+        const sdv2_chunk_desc& c = chunks[b];
+        if (c.stream_id < 0 || c.stream_id >= cache->cfg.n_streams) return fail(SDV2_INVALID_ARG, "stream %d out of range", c.stream_id);
+        for (int j = 0; j < b; ++j)
+            if (chunks[j].stream_id == c.stream_id) return fail(SDV2_INVALID_ARG, "stream %d listed twice", c.stream_id);
+        if (c.n_frames <= 0 || c.n_frames != chunks[0].n_frames) return fail(SDV2_INVALID_ARG, "n_frames must be positive and equal across streams");
+        if ((int64_t)c.n_frames * P > cache->cfg.window_tokens) return fail(SDV2_INVALID_ARG, "chunk larger than the window");
+        if (c.frame_pos0 < 0) return fail(SDV2_INVALID_ARG, "frame_pos0 < 0");
+        const size_t idx = (size_t)layer * cache->cfg.n_streams + c.stream_id;
+        if (!c.advance && cache->last_n[idx] != c.n_frames * P)
+            return fail(SDV2_BAD_STATE, "stream %d layer %d: advance = 0 without a matching append", c.stream_id, layer);
+    }
+    *L_out = chunks[0].n_frames * P;
+    return SDV2_OK;
+}
+
+void fill_rope_table(const sdv2_model_cfg* cfg, RopeAppendArgs* a) {
+    const int pairs = SDV2_HEAD_DIM / 2;
+    const int third = pairs / 3;
+    const int counts[3] = {pairs - 2 * third, third, third};
+    int p = 0;
+    for (int axis = 0; axis < 3; ++axis)
+        for (int j = 0; j < counts[axis]; ++j, ++p) {
+            a->pair_axis[p] = axis;
+            a->inv_freq[p] = pow((double)cfg->rope_base, -(double)j / counts[axis]);
+        }
+}
+
+// Launches one block.  State has been validated; it is advanced here and restored if a launch fails.
+int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_kv_cache* cache, int layer, float* x,
+                  const float* e0, const void* const* kt, const void* const* vtt, const sdv2_chunk_desc* chunks, int B,
+                  int L, const BlockWorkspace& ws, hipStream_t s) {
+    const int C = cfg->C, F = cfg->ffn_dim, H = cfg->n_heads;
+    const int rows = B * L;
+    const int S = cache->cfg.sink_tokens, W = cache->cfg.window_tokens;
+    int64_t old_total[SDV2_MAX_BATCH];
+    int32_t old_last[SDV2_MAX_BATCH];
+    RopeAppendArgs ra;
+    memset(&ra, 0, sizeof(ra));
+    AttnArgs at;
+    memset(&at, 0, sizeof(at));
+    int max_kv = 0;
+    for (int b = 0; b < B; ++b) {
+        const size_t idx = (size_t)layer * cache->cfg.n_streams + chunks[b].stream_id;
+        old_total[b] = cache->total[idx];
+        old_last[b] = cache->last_n[idx];
+        if (chunks[b].advance) {
+            cache->total[idx] += L;
+            cache->last_n[idx] = L;
+        }
+        ra.st[b] = append_stream(cache, layer, chunks[b].stream_id, cache->total[idx] - L, chunks[b].frame_pos0);
+        at.k[b] = ra.st[b].k_cache;
+        at.vt[b] = ra.st[b].vt_cache;
+        const int64_t res = cache->total[idx] < (int64_t)S + W ? cache->total[idx] : (int64_t)S + W;
+        at.kv_len[b] = (int)res;
+        at.cap[b] = cache->cap;
+        if (at.kv_len[b] > max_kv) max_kv = at.kv_len[b];
+    }
+    auto restore = [&]() {
+        for (int b = 0; b < B; ++b) {
+            const size_t idx = (size_t)layer * cache->cfg.n_streams + chunks[b].stream_id;
+            cache->total[idx] = old_total[b];
+            cache->last_n[idx] = old_last[b];
+        }
+    };
+#define RUN(tag, expr, what)                                              \
+    do {                                                                  \
+        hipError_t e__ = timed(tag, s, [&]() { return (expr); });         \
+        if (e__ != hipSuccess) {                                          \
+            restore();                                                    \
+            return hip_fail(e__, what);                                   \
+        }                                                                 \
+    } while (0)
+
+    const float* tab = w->mod_table;
+    LnArgs ln;
+    ln.x = x;
+    ln.out = ws.h;
+    ln.rows = rows;
+    ln.C = C;
+    ln.eps = cfg->eps;
+    ln.b_stride = 6 * C;
+    ln.rows_per_stream = L;
+    // 1. adaLN-1
+    ln.shift_a = tab + 0 * C;
+    ln.shift_b = e0 + 0 * C;
+    ln.scale_a = tab + 1 * C;
+    ln.scale_b = e0 + 1 * C;
+    RUN(SDV2_TAG_ADALN1, launch_layernorm(ln, s), "adaLN-1");
+    // 2. QKV projection
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.M = rows;
+    g.rows_per_gate = L;
+    g.gate_b_stride = 6 * C;
+    g.a = ws.h;
+    g.w = static_cast<const bf16*>(w->W_qkv);
+    g.bias = w->b_qkv;
+    g.out = ws.qkv;
+    g.N = 3 * C;
+    g.K = C;
+    g.epilogue = kEpiBias;
+    RUN(SDV2_TAG_QKV, launch_gemm(g, s), "QKV gemm");
+    // 3. q/k RMSNorm + RoPE + append into the ring
+    ra.qkv = ws.qkv;
+    ra.q_out = ws.q;
+    ra.g_q = w->g_q;
+    ra.g_k = w->g_k;
+    ra.B = B;
+    ra.L = L;
+    ra.C = C;
+    ra.H = H;
+    ra.tokens_per_frame = cfg->grid_h * cfg->grid_w;
+    ra.grid_w = cfg->grid_w;
+    ra.S = S;
+    ra.W = W;
+    ra.eps = cfg->eps;
+    fill_rope_table(cfg, &ra);
+    RUN(SDV2_TAG_ROPE_APPEND, launch_rope_append(ra, s), "rope + append");
+    // 4. self-attention over every resident slot
+    at.q = ws.q;
+    at.o = ws.o;
+    at.B = B;
+    at.L = L;
+    at.H = H;
+    at.splits = attention_plan_splits(B, L, H, max_kv);
+    at.part_o = ws.attn;
+    at.part_ml = ws.attn + (size_t)at.splits * rows * C;
+    RUN(SDV2_TAG_SELF_ATTN, launch_attention(at, s), "self-attention");
+    // 5. output projection, gated residual
+    g.a = ws.o;
+    g.w = static_cast<const bf16*>(w->W_o);
+    g.bias = w->b_o;
+    g.out = x;
+    g.N = C;
+    g.K = C;
+    g.epilogue = kEpiGatedResidual;
+    g.gate_a = tab + 2 * C;
+    g.gate_b = e0 + 2 * C;
+    RUN(SDV2_TAG_OUT_PROJ, launch_gemm(g, s), "out-proj gemm");
+    // 6. LayerNorm-3 (affine) and the cross-attention query
+    ln.scale_a = w->ln3_gamma;
+    ln.scale_b = nullptr;
+    ln.shift_a = w->ln3_beta;
+    ln.shift_b = nullptr;
+    RUN(SDV2_TAG_LN3, launch_layernorm(ln, s), "LN-3");
+    g.a = ws.h;
+    g.w = static_cast<const bf16*>(w->W_cq);
+    g.bias = w->b_cq;
+    g.out = ws.q;
+    g.epilogue = kEpiBias;
+    RUN(SDV2_TAG_CROSS_Q, launch_gemm(g, s), "cross-q gemm");
+    RUN(SDV2_TAG_CROSS_Q_NORM, launch_rmsnorm_inplace(ws.q, w->g_cq, rows, C, C, cfg->eps, s), "cross-q norm");
+    // 7. cross-attention over the text tokens
+    AttnArgs ct = at;
+    const int cap_t = (int)align_up((size_t)cfg->text_len, 64);
+    for (int b = 0; b < B; ++b) {
+        ct.k[b] = static_cast<const bf16*>(kt[b]);
+        ct.vt[b] = static_cast<const bf16*>(vtt[b]);
+        ct.kv_len[b] = cfg->text_len;
+        ct.cap[b] = cap_t;
+    }
+    ct.splits = attention_plan_splits(B, L, H, cfg->text_len);
+    ct.part_ml = ws.attn + (size_t)ct.splits * rows * C;
+    RUN(SDV2_TAG_CROSS_ATTN, launch_attention(ct, s), "cross-attention");
+    g.a = ws.o;
+    g.w = static_cast<const bf16*>(w->W_co);
+    g.bias = w->b_co;
+    g.out = x;
+    g.epilogue = kEpiResidual;
+    RUN(SDV2_TAG_CROSS_OUT, launch_gemm(g, s), "cross-out gemm");
+    // 8. adaLN-2 and the FFN
+    ln.shift_a = tab + 3 * C;
+    ln.shift_b = e0 + 3 * C;
+    ln.scale_a = tab + 4 * C;
+    ln.scale_b = e0 + 4 * C;
+    RUN(SDV2_TAG_ADALN2, launch_layernorm(ln, s), "adaLN-2");
+    g.a = ws.h;
+    g.w = static_cast<const bf16*>(w->W_1);
+    g.bias = w->b_1;
+    g.out = ws.u;
+    g.N = F;
+    g.K = C;
+    g.epilogue = kEpiBiasGelu;
+    RUN(SDV2_TAG_FFN1, launch_gemm(g, s), "FFN-1 gemm");
+    g.a = ws.u;
+    g.w = static_cast<const bf16*>(w->W_2);
+    g.bias = w->b_2;
+    g.out = x;
+    g.N = C;
+    g.K = F;
+    g.epilogue = kEpiGatedResidual;
+    g.gate_a = tab + 5 * C;
+    g.gate_b = e0 + 5 * C;
+    RUN(SDV2_TAG_FFN2, launch_gemm(g, s), "FFN-2 gemm");
+#undef RUN
+    return SDV2_OK;
+}
+
+int max_kv_possible(const sdv2_kv_cache* cache) { return cache->cfg.sink_tokens + cache->cfg.window_tokens; }
+
+}  // namespace
+
+extern "C" {
+
+size_t sdv2_block_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why) || B <= 0 || B > SDV2_MAX_BATCH || L <= 0) {
+        fail(SDV2_INVALID_ARG, "bad cfg, B or L");
+        return 0;
+    }
+    // sized for the largest split plan any cache length can ask for
+    size_t worst = 0;
+    for (int kv = 64; kv <= (1 << 20); kv *= 2) {
+        const size_t t = carve_block(cfg, B, L, kv, nullptr).total;
+        if (t > worst) worst = t;
+    }
+    return worst;
+}
+
+int32_t sdv2_dit_block_forward(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_kv_cache* cache,
+                               int32_t layer, float* x_dev, const float* e0_dev, const void* const* kt_dev,
+                               const void* const* vtt_dev, const sdv2_chunk_desc* chunks, int32_t B,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    int L = 0;
+    int32_t rc = validate_block_call(cfg, w, cache, layer, chunks, B, &L);
+    if (rc) return rc;
+    if (!x_dev || !e0_dev || !kt_dev || !vtt_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    for (int b = 0; b < B; ++b)
+        if (!kt_dev[b] || !vtt_dev[b]) return fail(SDV2_INVALID_ARG, "text K/V of stream slot %d is null", b);
+    const size_t need = sdv2_block_workspace_bytes(cfg, B, L);
+    if (workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    const BlockWorkspace ws = carve_block(cfg, B, L, max_kv_possible(cache), static_cast<unsigned char*>(workspace_dev));
+    return run_block(cfg, w, cache, layer, x_dev, e0_dev, kt_dev, vtt_dev, chunks, B, L, ws,
+                     static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sdv2_denoise_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L) {
+    const size_t blk = sdv2_block_workspace_bytes(cfg, B, L);
+    if (!blk) return 0;
+    return blk + align_up((size_t)B * 6 * cfg->C * 4, 256) + sdv2_conditioning_workspace_bytes(cfg, B);
+}
+
+int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache, float* x_dev,
+                          const float* timesteps_host, const float* tvec_dev, const void* const* kt_dev,
+                          const void* const* vtt_dev, const sdv2_chunk_desc* chunks, int32_t B, void* workspace_dev,
+                          size_t workspace_bytes, void* hip_stream) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!mw || mw->struct_size != sizeof(sdv2_model_weights) || !mw->blocks) return fail(SDV2_INVALID_ARG, "bad model weights");
+    if (!cache || cache->cfg.n_layers != cfg->n_layers) return fail(SDV2_INVALID_ARG, "cache and model layer counts disagree");
+    if ((timesteps_host == nullptr) == (tvec_dev == nullptr))
+        return fail(SDV2_INVALID_ARG, "give exactly one of timesteps_host and tvec_dev");
+    if (!x_dev || !kt_dev || !vtt_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    int L = 0;
+    for (int layer = 0; layer < cfg->n_layers; ++layer) {
+        int32_t rc = validate_block_call(cfg, &mw->blocks[layer], cache, layer, chunks, B, &L);
+        if (rc) return rc;
+        for (int b = 0; b < B; ++b)
+            if (!kt_dev[(size_t)layer * B + b] || !vtt_dev[(size_t)layer * B + b])
+                return fail(SDV2_INVALID_ARG, "text K/V of layer %d slot %d is null", layer, b);
+    }
+    const size_t need = sdv2_denoise_workspace_bytes(cfg, B, L);
+    if (workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    unsigned char* p = static_cast<unsigned char*>(workspace_dev);
+    const size_t blk = sdv2_block_workspace_bytes(cfg, B, L);
+    float* e0 = reinterpret_cast<float*>(p + blk);
+    void* cond_ws = p + blk + align_up((size_t)B * 6 * cfg->C * 4, 256);
+    int32_t rc = sdv2_conditioning(cfg, mw, B, timesteps_host, tvec_dev, e0, cond_ws,
+                                   sdv2_conditioning_workspace_bytes(cfg, B), hip_stream);
+    if (rc) return rc;
+    const BlockWorkspace ws = carve_block(cfg, B, L, max_kv_possible(cache), p);
+    for (int layer = 0; layer < cfg->n_layers; ++layer) {
+        rc = run_block(cfg, &mw->blocks[layer], cache, layer, x_dev, e0, kt_dev + (size_t)layer * B,
+                       vtt_dev + (size_t)layer * B, chunks, B, L, ws, s);
+        if (rc) return rc;
+    }
+    return SDV2_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------ profiling helpers
+extern "C" {
+
+int32_t sdv2_prof_begin(int32_t max_samples) {
+    if (max_samples <= 0 || max_samples > (1 << 20)) return fail(SDV2_INVALID_ARG, "max_samples out of range");
+    if (g_prof.on) return fail(SDV2_BAD_STATE, "profiling already on");
+    g_prof.start.resize(max_samples);
+    g_prof.stop.resize(max_samples);
+    g_prof.tag.assign(max_samples, -1);
+    for (int i = 0; i < max_samples; ++i) {
+        HIP_TRY(hipEventCreate(&g_prof.start[i]), "event create");
+        HIP_TRY(hipEventCreate(&g_prof.stop[i]), "event create");
+    }
+    g_prof.n = 0;
+    g_prof.on = true;
+    return SDV2_OK;
+}
+
+int32_t sdv2_prof_end(int32_t* tags_out, float* ms_out, int32_t capacity, int32_t* n_out) {
+    if (!g_prof.on) return fail(SDV2_BAD_STATE, "profiling is not on");
+    if (!tags_out || !ms_out || !n_out) return fail(SDV2_INVALID_ARG, "null pointer");
+    g_prof.on = false;
+    int32_t rc = SDV2_OK;
+    const int n = g_prof.n < capacity ? g_prof.n : capacity;
+    for (int i = 0; i < n && rc == SDV2_OK; ++i) {
+        hipError_t e = hipEventSynchronize(g_prof.stop[i]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms_out[i], g_prof.start[i], g_prof.stop[i]);
+        if (e != hipSuccess) rc = hip_fail(e, "event elapsed");
+        tags_out[i] = g_prof.tag[i];
+    }
+    *n_out = n;
+    for (size_t i = 0; i < g_prof.start.size(); ++i) {
+        hipEventDestroy(g_prof.start[i]);
+        hipEventDestroy(g_prof.stop[i]);
+    }
+    g_prof.start.clear();
+    g_prof.stop.clear();
+    g_prof.n = 0;
+    return rc;
+}
+
+}  // extern "C"

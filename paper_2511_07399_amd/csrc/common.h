@@ -1,0 +1,128 @@
+// Internal declarations shared by the HIP sources of libsdv2 (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sdv2 {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kHeadDim = 128;
+constexpr int kMaxBatch = 8;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float gelu_tanh_f(float x) {
+    // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return x / (1.0f + __expf(-2.0f * u));
+}
+
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+
+// ---------------------------------------------------------------- launchers (host side)
+enum GemmEpilogue { kEpiBias = 0, kEpiBiasGelu = 1, kEpiGatedResidual = 2, kEpiResidual = 3 };
+
+struct GemmArgs {
+    const bf16* a;        // [M, K]
+    const bf16* w;        // [N, K]
+    const float* bias;    // [N] or null
+    void* out;            // bf16 [M, N] (epilogue 0, 1) or fp32 [M, N] (2, 3)
+    int M, N, K;
+    int epilogue;
+    const float* gate_a;  // [N]
+    const float* gate_b;  // [(M / rows_per_gate), gate_b_stride]
+    int gate_b_stride;
+    int rows_per_gate;
+};
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+
+struct AttnArgs {
+    const bf16* q;                    // [B, L, C]
+    const bf16* k[kMaxBatch];         // [H][cap][128]
+    const bf16* vt[kMaxBatch];        // [H][128][cap]
+    int kv_len[kMaxBatch];
+    int cap[kMaxBatch];
+    bf16* o;                          // [B, L, C]
+    int B, L, H;
+    float* part_o;                    // workspace: [splits][B*L][C] fp32
+    float* part_ml;                   // workspace: [splits][B*L][H][2] fp32
+    int splits;                       // chosen by attention_plan
+};
+int attention_plan_splits(int B, int L, int H, int max_kv_len);
+size_t attention_workspace_bytes(int B, int L, int C, int max_kv_len);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+
+// LayerNorm over C with an affine that is either adaLN modulation or a plain (gamma, beta).
+struct LnArgs {
+    const float* x;       // [rows, C]
+    bf16* out;            // [rows, C]
+    int rows, C;
+    float eps;
+    // scale = 1 + (scale_a[c] + scale_b[stream * b_stride + c]) when modulated, gamma[c] otherwise
+    const float* scale_a;
+    const float* scale_b; // null: plain affine (scale_a = gamma, shift_a = beta)
+    const float* shift_a;
+    const float* shift_b;
+    int b_stride;
+    int rows_per_stream;
+};
+hipError_t launch_layernorm(const LnArgs& a, hipStream_t s);
+
+// In-place RMSNorm over C of bf16 rows, times gain.
+hipError_t launch_rmsnorm_inplace(bf16* x, const float* gain, int rows, int C, int ld, float eps, hipStream_t s);
+
+// q/k RMSNorm + 3D-RoPE + append of k and v into the rolling cache.
+struct AppendStream {
+    bf16* k_cache;        // [H][cap][128]
+    bf16* vt_cache;       // [H][128][cap]
+    long long* ids;       // [cap]
+    long long g0;         // token id of the chunk's first token
+    int frame_pos0;
+    int cap;
+};
+struct RopeAppendArgs {
+    const bf16* qkv;      // [B*L, 3C]   (or separate k, v when q_out == null)
+    bf16* q_out;          // [B*L, C]
+    const float* g_q;
+    const float* g_k;
+    int B, L, C, H;
+    int tokens_per_frame, grid_w;
+    int S, W;
+    float eps;
+    double inv_freq[kHeadDim / 2];    // rotation frequency of each pair of a head
+    int pair_axis[kHeadDim / 2];      // 0 frame, 1 row, 2 col
+    AppendStream st[kMaxBatch];
+};
+hipError_t launch_rope_append(const RopeAppendArgs& a, hipStream_t s);
+
+// Plain append of final k, v rows [n, C] (standalone cache call).
+struct PlainAppendArgs {
+    const bf16* k;        // [n, C]
+    const bf16* v;        // [n, C]
+    int n, C, H, S, W;
+    AppendStream st;
+};
+hipError_t launch_plain_append(const PlainAppendArgs& a, hipStream_t s);
+
+// Re-layout of text K/V rows [L_t, C] into the cache layouts.
+hipError_t launch_text_relayout(const bf16* k_rows, const bf16* v_rows, bf16* kt, bf16* vtt,
+                                int L_t, int C, int H, int cap, hipStream_t s);
+
+// y[b][n] = act_out(sum_k act_in(x[b][k]) W[n][k] + bias[n]); x, y fp32; W bf16 [N, K]; B <= kMaxBatch.
+hipError_t launch_gemv(const float* x, const bf16* w, const float* bias, float* y, int B, int N, int K,
+                       int silu_in, hipStream_t s);
+hipError_t launch_timestep_embedding(const float* t_dev, float* emb, int B, int t_dim, double base, hipStream_t s);
+
+}  // namespace sdv2

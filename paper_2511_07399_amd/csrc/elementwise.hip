@@ -1,0 +1,349 @@
+// HBM-bound kernels of the block: LayerNorm with adaLN modulation, RMSNorm, the fused
+// q/k RMSNorm + 3D-RoPE + rolling-cache append, cache re-layouts and the small conditioning GEMVs.
+//
+// These are the "36 b L_q C" activation bytes and the "4 b L_q C" cache write of the memory model
+// in Appendix B of the paper.  The paper's implementation also pays for sliding-window buffering and
+// concatenation (its measured extra traffic gamma); here a chunk's keys and values are written once,
+// straight into their ring slots, and nothing is ever moved.
+//
+// All row reductions are one wavefront per row with cross-lane shuffles; no LDS, no atomics.
+#include "common.h"
+
+namespace sdv2 {
+
+namespace {
+
+// physical slot of token id g:  g in the sink, else ring position
+__device__ __forceinline__ int slot_of(long long g, int S, int W) {
+    return g < S ? (int)g : S + (int)((g - S) % W);
+}
+
+// ------------------------------------------------------------------ LayerNorm (+ modulation or affine)
+// LN_MAXV = float4 values a lane keeps in registers: C <= 256 * LN_MAXV.
+template <int LN_MAXV>
+__global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.rows) return;
+    const int nvec = a.C >> 2;
+    const f32x4* xp = reinterpret_cast<const f32x4*>(a.x + (size_t)row * a.C);
+    f32x4 v[LN_MAXV];
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+        const int idx = lane + 64 * i;
+        if (idx < nvec) {
+            v[i] = xp[idx];
+            sum += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+        }
+    }
+    const float mean = wave_sum(sum) / (float)a.C;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+        const int idx = lane + 64 * i;
+        if (idx < nvec) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float d = v[i][e] - mean;
+                sq += d * d;
+            }
+        }
+    }
+    const float rstd = rsqrtf(wave_sum(sq) / (float)a.C + a.eps);
+    const int stream = row / a.rows_per_stream;
+    bf16* op = a.out + (size_t)row * a.C;
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+        const int idx = lane + 64 * i;
+        if (idx < nvec) {
+            const int c = idx * 4;
+            f32x4 sc = *reinterpret_cast<const f32x4*>(a.scale_a + c);
+            f32x4 sh = *reinterpret_cast<const f32x4*>(a.shift_a + c);
+            if (a.scale_b != nullptr) {
+                sc += *reinterpret_cast<const f32x4*>(a.scale_b + (size_t)stream * a.b_stride + c);
+                sh += *reinterpret_cast<const f32x4*>(a.shift_b + (size_t)stream * a.b_stride + c);
+                sc += 1.0f;
+            }
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)((v[i][e] - mean) * rstd * sc[e] + sh[e]);
+            *reinterpret_cast<bf16x4*>(op + c) = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ RMSNorm in place on bf16 rows
+__global__ __launch_bounds__(256) void rmsnorm_inplace_kernel(bf16* x, const float* gain, int rows, int C, int ld,
+                                                              float eps) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    bf16* xp = x + (size_t)row * ld;
+    const int nvec = C >> 3;
+    float sq = 0.0f;
+    for (int idx = lane; idx < nvec; idx += 64) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(xp + idx * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sq += (float)v[e] * (float)v[e];
+    }
+    const float r = rsqrtf(wave_sum(sq) / (float)C + eps);
+    for (int idx = lane; idx < nvec; idx += 64) {
+        bf16x8 v = *reinterpret_cast<const bf16x8*>(xp + idx * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (bf16)((float)v[e] * r * gain[idx * 8 + e]);
+        *reinterpret_cast<bf16x8*>(xp + idx * 8) = v;
+    }
+}
+
+// ------------------------------------------------------------------ q/k RMSNorm + RoPE + append, and V^T append
+// Blocks [0, norm_blocks): one wave per token.  Lane j owns rotation pair j of every head: it reads
+// (x[2j], x[2j+1]) of q and k head by head (256 contiguous bytes per wave and head), reduces the sums
+// of squares over the whole row, then normalises, rotates and writes q to its buffer and k to the
+// token's ring slot.  The rotation angle is formed in double so that it stays exact for any stream
+// length.
+// Blocks [norm_blocks, ...): one (64-token tile, head) each: v goes through LDS and is written
+// transposed, slot index contiguous, into the V^T cache.
+constexpr int VT_TOK = 64;
+constexpr int VT_LD = kHeadDim + 2;     // LDS row stride in elements: odd number of words, no bank conflicts
+
+__global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs a, int norm_blocks, int tiles_per_stream) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int C = a.C;
+    if ((int)blockIdx.x < norm_blocks) {
+        const int row = blockIdx.x * 4 + wave;               // over B * L
+        if (row >= a.B * a.L) return;
+        const int b = row / a.L;
+        const int i = row - b * a.L;
+        const AppendStream& st = a.st[b];
+        const bf16* qp = a.qkv + (size_t)row * 3 * C;
+        const bf16* kp = qp + C;
+        float sq = 0.0f, sk = 0.0f;
+        for (int h = 0; h < a.H; ++h) {
+            const bf16x2 qv = *reinterpret_cast<const bf16x2*>(qp + h * kHeadDim + 2 * lane);
+            const bf16x2 kv = *reinterpret_cast<const bf16x2*>(kp + h * kHeadDim + 2 * lane);
+            sq += (float)qv[0] * (float)qv[0] + (float)qv[1] * (float)qv[1];
+            sk += (float)kv[0] * (float)kv[0] + (float)kv[1] * (float)kv[1];
+        }
+        const float rq = rsqrtf(wave_sum(sq) / (float)C + a.eps);
+        const float rk = rsqrtf(wave_sum(sk) / (float)C + a.eps);
+        // position of the token and this lane's rotation
+        const int frame = st.frame_pos0 + i / a.tokens_per_frame;
+        const int inside = i % a.tokens_per_frame;
+        const int axis = a.pair_axis[lane];
+        const int pos = axis == 0 ? frame : (axis == 1 ? inside / a.grid_w : inside % a.grid_w);
+        double sn, cs;
+        sincos((double)pos * a.inv_freq[lane], &sn, &cs);
+        const float cf = (float)cs, sf = (float)sn;
+        const long long g = st.g0 + i;
+        const int slot = slot_of(g, a.S, a.W);
+        if (lane == 0) st.ids[slot] = g;
+        bf16* qo = a.q_out + (size_t)row * C;
+        for (int h = 0; h < a.H; ++h) {
+            const int c = h * kHeadDim + 2 * lane;
+            const bf16x2 qv = *reinterpret_cast<const bf16x2*>(qp + c);
+            const bf16x2 kv = *reinterpret_cast<const bf16x2*>(kp + c);
+            const float q0 = (float)qv[0] * rq * a.g_q[c], q1 = (float)qv[1] * rq * a.g_q[c + 1];
+            const float k0 = (float)kv[0] * rk * a.g_k[c], k1 = (float)kv[1] * rk * a.g_k[c + 1];
+            bf16x2 qr, kr;
+            qr[0] = (bf16)(q0 * cf - q1 * sf);
+            qr[1] = (bf16)(q0 * sf + q1 * cf);
+            kr[0] = (bf16)(k0 * cf - k1 * sf);
+            kr[1] = (bf16)(k0 * sf + k1 * cf);
+            *reinterpret_cast<bf16x2*>(qo + c) = qr;
+            *reinterpret_cast<bf16x2*>(st.k_cache + ((size_t)h * st.cap + slot) * kHeadDim + 2 * lane) = kr;
+        }
+        return;
+    }
+    // ---- V^T tiles
+    __shared__ bf16 tile[VT_TOK * VT_LD];
+    const int vb = blockIdx.x - norm_blocks;
+    const int h = vb % a.H;
+    const int tile_id = vb / a.H;
+    const int b = tile_id / tiles_per_stream;
+    const int tok0 = (tile_id - b * tiles_per_stream) * VT_TOK;
+    const AppendStream& st = a.st[b];
+    // read: 64 tokens x 128 channels, 16-byte chunks, stored to LDS as 4-byte words
+    for (int idx = threadIdx.x; idx < VT_TOK * 16; idx += 256) {
+        const int tok = idx >> 4, c = idx & 15;
+        if (tok0 + tok < a.L) {
+            const bf16* vp = a.qkv + ((size_t)b * a.L + tok0 + tok) * 3 * C + 2 * C + h * kHeadDim + c * 8;
+            const bf16x8 v = *reinterpret_cast<const bf16x8*>(vp);
+            bf16x2* dst = reinterpret_cast<bf16x2*>(tile + tok * VT_LD + c * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[e] = bf16x2{v[2 * e], v[2 * e + 1]};
+        }
+    }
+    __syncthreads();
+    // write: lane = token, each wave takes 32 of the 128 channels
+    const int tok = lane;
+    if (tok0 + tok < a.L) {
+        const int slot = slot_of(st.g0 + tok0 + tok, a.S, a.W);
+        bf16* vo = st.vt_cache + (size_t)h * kHeadDim * st.cap + slot;
+        for (int d = wave * 32; d < wave * 32 + 32; ++d) vo[(size_t)d * st.cap] = tile[tok * VT_LD + d];
+    }
+}
+
+// ------------------------------------------------------------------ plain append of final rows
+__global__ __launch_bounds__(256) void plain_append_kernel(PlainAppendArgs a, int k_blocks) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int C = a.C;
+    if ((int)blockIdx.x < k_blocks) {
+        const int row = blockIdx.x * 4 + wave;
+        if (row >= a.n) return;
+        const long long g = a.st.g0 + row;
+        const int slot = slot_of(g, a.S, a.W);
+        if (lane == 0 && a.st.ids != nullptr) a.st.ids[slot] = g;
+        for (int h = 0; h < a.H; ++h) {
+            const bf16x2 kv = *reinterpret_cast<const bf16x2*>(a.k + (size_t)row * C + h * kHeadDim + 2 * lane);
+            *reinterpret_cast<bf16x2*>(a.st.k_cache + ((size_t)h * a.st.cap + slot) * kHeadDim + 2 * lane) = kv;
+        }
+        return;
+    }
+    __shared__ bf16 tile[VT_TOK * VT_LD];
+    const int vb = blockIdx.x - k_blocks;
+    const int h = vb % a.H;
+    const int tok0 = (vb / a.H) * VT_TOK;
+    for (int idx = threadIdx.x; idx < VT_TOK * 16; idx += 256) {
+        const int tok = idx >> 4, c = idx & 15;
+        if (tok0 + tok < a.n) {
+            const bf16x8 v = *reinterpret_cast<const bf16x8*>(a.v + (size_t)(tok0 + tok) * C + h * kHeadDim + c * 8);
+            bf16x2* dst = reinterpret_cast<bf16x2*>(tile + tok * VT_LD + c * 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[e] = bf16x2{v[2 * e], v[2 * e + 1]};
+        }
+    }
+    __syncthreads();
+    const int tok = lane;
+    if (tok0 + tok < a.n) {
+        const int slot = slot_of(a.st.g0 + tok0 + tok, a.S, a.W);
+        bf16* vo = a.st.vt_cache + (size_t)h * kHeadDim * a.st.cap + slot;
+        for (int d = wave * 32; d < wave * 32 + 32; ++d) vo[(size_t)d * a.st.cap] = tile[tok * VT_LD + d];
+    }
+}
+
+// ------------------------------------------------------------------ conditioning
+struct TimestepArgs {
+    float t[kMaxBatch];
+};
+
+__global__ void timestep_embedding_kernel(TimestepArgs ts, float* emb, int B, int t_dim, double log2_base) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * t_dim) return;
+    const int b = idx / t_dim;
+    const int j = idx - b * t_dim;
+    const int half = t_dim / 2;
+    const int jj = j < half ? j : j - half;
+    const double w = exp2(-log2_base * (double)jj / (double)half);
+    const double arg = (double)ts.t[b] * w;
+    emb[idx] = (float)(j < half ? cos(arg) : sin(arg));
+}
+
+// one wave per output n; the B input rows reuse each weight row
+__global__ __launch_bounds__(256) void gemv_kernel(const float* x, const bf16* w, const float* bias, float* y, int B,
+                                                   int N, int K, int silu_in) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    float acc[kMaxBatch];
+#pragma unroll
+    for (int b = 0; b < kMaxBatch; ++b) acc[b] = 0.0f;
+    const bf16* wp = w + (size_t)n * K;
+    for (int k = lane * 8; k < K; k += 64 * 8) {
+        const bf16x8 wv = *reinterpret_cast<const bf16x8*>(wp + k);
+#pragma unroll
+        for (int b = 0; b < kMaxBatch; ++b) {
+            if (b < B) {
+                const float* xp = x + (size_t)b * K + k;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float xv = xp[e];
+                    if (silu_in) xv = silu_f(xv);
+                    acc[b] += xv * (float)wv[e];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < kMaxBatch; ++b) {
+        if (b < B) {
+            const float s = wave_sum(acc[b]);
+            if (lane == 0) y[(size_t)b * N + n] = s + bias[n];
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_layernorm(const LnArgs& a, hipStream_t s) {
+    const dim3 grid((a.rows + 3) / 4), block(256);
+    const int nv = (a.C + 255) / 256;
+    if (nv <= 2) hipLaunchKernelGGL(layernorm_kernel<2>, grid, block, 0, s, a);
+    else if (nv <= 6) hipLaunchKernelGGL(layernorm_kernel<6>, grid, block, 0, s, a);
+    else if (nv <= 8) hipLaunchKernelGGL(layernorm_kernel<8>, grid, block, 0, s, a);
+    else if (nv <= 12) hipLaunchKernelGGL(layernorm_kernel<12>, grid, block, 0, s, a);
+    else if (nv <= 20) hipLaunchKernelGGL(layernorm_kernel<20>, grid, block, 0, s, a);
+    else if (nv <= 32) hipLaunchKernelGGL(layernorm_kernel<32>, grid, block, 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_inplace(bf16* x, const float* gain, int rows, int C, int ld, float eps, hipStream_t s) {
+    hipLaunchKernelGGL(rmsnorm_inplace_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, x, gain, rows, C, ld, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_append(const RopeAppendArgs& a, hipStream_t s) {
+    const int norm_blocks = (a.B * a.L + 3) / 4;
+    const int tiles_per_stream = (a.L + VT_TOK - 1) / VT_TOK;
+    const int v_blocks = a.B * tiles_per_stream * a.H;
+    hipLaunchKernelGGL(rope_append_kernel, dim3(norm_blocks + v_blocks), dim3(256), 0, s, a, norm_blocks,
+                       tiles_per_stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_plain_append(const PlainAppendArgs& a, hipStream_t s) {
+    const int k_blocks = (a.n + 3) / 4;
+    const int v_blocks = ((a.n + VT_TOK - 1) / VT_TOK) * a.H;
+    hipLaunchKernelGGL(plain_append_kernel, dim3(k_blocks + v_blocks), dim3(256), 0, s, a, k_blocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_text_relayout(const bf16* k_rows, const bf16* v_rows, bf16* kt, bf16* vtt, int L_t, int C, int H,
+                                int cap, hipStream_t s) {
+    // the text K/V buffers are a cache with no ring: slot = token index
+    PlainAppendArgs a;
+    a.k = k_rows;
+    a.v = v_rows;
+    a.n = L_t;
+    a.C = C;
+    a.H = H;
+    a.S = cap;          // every token is "sink": slot(g) = g
+    a.W = 1;
+    a.st.k_cache = kt;
+    a.st.vt_cache = vtt;
+    a.st.ids = nullptr;
+    a.st.g0 = 0;
+    a.st.frame_pos0 = 0;
+    a.st.cap = cap;
+    return launch_plain_append(a, s);
+}
+
+hipError_t launch_gemv(const float* x, const bf16* w, const float* bias, float* y, int B, int N, int K, int silu_in,
+                       hipStream_t s) {
+    hipLaunchKernelGGL(gemv_kernel, dim3((N + 3) / 4), dim3(256), 0, s, x, w, bias, y, B, N, K, silu_in);
+    return hipGetLastError();
+}
+
+hipError_t launch_timestep_embedding(const float* t_host, float* emb, int B, int t_dim, double base, hipStream_t s) {
+    TimestepArgs ts;
+    for (int b = 0; b < kMaxBatch; ++b) ts.t[b] = b < B ? t_host[b] : 0.0f;
+    const int n = B * t_dim;
+    hipLaunchKernelGGL(timestep_embedding_kernel, dim3((n + 255) / 256), dim3(256), 0, s, ts, emb, B, t_dim,
+                       log2(base));
+    return hipGetLastError();
+}
+
+}  // namespace sdv2

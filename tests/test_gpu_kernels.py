@@ -1,0 +1,217 @@
+"""GPU parity of the individual kernels, through the C ABI, against the CPU oracle.
+
+Tolerances: the dense kernels multiply bf16 operands exactly and accumulate in fp32, so against the
+float64 oracle on the same bf16 inputs the only errors are fp32 summation order (relative 1e-6 per
+term) and the final rounding of the output to bf16 (relative 2^-9).  Attention also rounds the
+probabilities to bf16 before the second product.  Bars: 1e-2 of the largest output for bf16 outputs,
+1e-4 for fp32 outputs; cache bookkeeping and copied cache contents are bit-exact.
+"""
+
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle.dit_block import linear as oracle_linear
+from paper_2511_07399_amd import binding
+from parity_util import max_rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bf16_randn(shape, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(shape, generator=g) * scale).to(torch.bfloat16)
+
+
+def f64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+# ------------------------------------------------------------------------------------------ GEMM
+GEMM_CASES = [
+    # M, N, K, epilogue, tile override (tm,tn,splitk) or None
+    (128, 128, 64, 0, None),
+    (1, 128, 64, 0, None),                 # a single row
+    (200, 384, 192, 0, "1,3,1"),           # ragged M, N tile of 96
+    (333, 640, 512, 1, "2,5,1"),           # GELU epilogue, 256 x 160 tiles, ragged M
+    (1024, 1536, 512, 0, "1,7,1"),         # N not a multiple of the 224-wide tile
+    (300, 512, 1024, 2, "1,4,2"),          # gated residual, split-K atomics, ragged M
+    (300, 512, 1024, 2, None),
+    (260, 256, 2048, 3, "2,8,4"),          # residual, biggest tile, split-K 4
+    (1024, 2048, 512, 1, None),            # tiny workload FFN-1
+    (1024, 4608, 1536, 0, None),           # 1.3B QKV
+    (1024, 1536, 8960, 2, None),           # 1.3B FFN-2 (planner's own tile and split)
+]
+
+
+@pytest.mark.parametrize("M,N,K,epi,tile", GEMM_CASES)
+def test_gemm_matches_oracle(M, N, K, epi, tile):
+    a = bf16_randn((M, K), 1)
+    w = bf16_randn((N, K), 2, 0.05)
+    bias = bf16_randn((N,), 3, 0.5).float()
+    rows_per_gate = max(M // 3, 1)
+    n_gate = (M + rows_per_gate - 1) // rows_per_gate
+    gate_a = bf16_randn((N,), 4, 0.3).float()
+    gate_b = bf16_randn((n_gate, 2 * N), 5, 0.3).float()        # stride 2N: a strided table
+    x0 = bf16_randn((M, N), 6).float()
+    acc = oracle_linear(f64(a), f64(w), f64(bias))
+    if epi == 0:
+        want = acc
+    elif epi == 1:
+        want = oracle.gelu_tanh(acc)
+    elif epi == 2:
+        gate = f64(gate_a)[None, :] + f64(gate_b)[np.arange(M) // rows_per_gate, :N]
+        want = f64(x0) + gate * acc
+    else:
+        want = f64(x0) + acc
+    out = (torch.empty(M, N, dtype=torch.bfloat16) if epi < 2 else x0.clone()).to(DEV)
+    if tile:
+        os.environ["SDV2_GEMM_TILE"] = tile
+    try:
+        binding.gemm_bf16(a.to(DEV), w.to(DEV), bias.to(DEV), out, epi, gate_a.to(DEV), gate_b.to(DEV), 2 * N,
+                          rows_per_gate)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("SDV2_GEMM_TILE", None)
+    err = max_rel_err(f64(out), want)
+    assert err < (1e-2 if epi < 2 else 1e-4), err
+
+
+def test_gemm_rejects_bad_shapes():
+    a = torch.zeros(8, 100, dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros(128, 100, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(8, 128, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(binding.Sdv2Error) as e:
+        binding.gemm_bf16(a, w, None, out)
+    assert e.value.code == binding.INVALID_ARG
+
+
+# ------------------------------------------------------------------------------------------ attention
+def pack_kv(k_rows, v_rows, H, cap):
+    """Token rows [n, C] -> the cache layouts K [H][cap][128], V^T [H][128][cap]; padding slots are NaN."""
+    n, Cw = k_rows.shape
+    D = Cw // H
+    K = torch.full((H, cap, D), float("nan"), dtype=torch.bfloat16)
+    VT = torch.full((H, D, cap), float("nan"), dtype=torch.bfloat16)
+    K[:, :n, :] = k_rows.reshape(n, H, D).permute(1, 0, 2)
+    VT[:, :, :n] = v_rows.reshape(n, H, D).permute(1, 2, 0)
+    return K.contiguous(), VT.contiguous()
+
+
+ATTN_CASES = [
+    # B, L, H, kv_lens, forced splits
+    (1, 128, 1, [64], 0),
+    (1, 32, 2, [1], 0),                    # a single key
+    (1, 100, 2, [63], 0),                  # ragged queries and keys inside one tile
+    (1, 130, 2, [65], 0),                  # one key into the second tile
+    (2, 300, 3, [384, 129], 0),            # two streams with different lengths
+    (1, 128, 4, [384], 3),                 # split-KV, merged
+    (2, 200, 2, [1000, 70], 4),            # a stream with fewer tiles than splits
+    (1, 1024, 12, [3072], 0),              # 1.3B steady state (planner's split)
+    (1, 1024, 12, [512], 0),               # text cross-attention shape
+]
+
+
+@pytest.mark.parametrize("B,L,H,kv_lens,splits", ATTN_CASES)
+def test_attention_matches_oracle(B, L, H, kv_lens, splits):
+    D = 128
+    Cw = H * D
+    q = bf16_randn((B, L, Cw), 10)
+    ks, vts, caps, want = [], [], [], []
+    for b, n in enumerate(kv_lens):
+        k_rows = bf16_randn((n, Cw), 20 + b)
+        v_rows = bf16_randn((n, Cw), 30 + b)
+        cap = (n + 63) // 64 * 64 + 64 * (b % 2)
+        K, VT = pack_kv(k_rows, v_rows, H, cap)
+        ks.append(K.to(DEV))
+        vts.append(VT.to(DEV))
+        caps.append(cap)
+        want.append(oracle.attention_dense(f64(q[b]).reshape(L, H, D), f64(k_rows).reshape(n, H, D),
+                                           f64(v_rows).reshape(n, H, D)).reshape(L, Cw))
+    o = torch.full((B, L, Cw), float("nan"), dtype=torch.bfloat16, device=DEV)
+    if splits:
+        os.environ["SDV2_ATTN_SPLITS"] = str(splits)
+    try:
+        ws = torch.empty(max(binding.attention_workspace_bytes(B, L, Cw, max(kv_lens)), 256), dtype=torch.uint8, device=DEV)
+        binding.attention_bf16(q.to(DEV), ks, vts, kv_lens, caps, o, H, ws)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("SDV2_ATTN_SPLITS", None)
+    got = f64(o)
+    assert np.isfinite(got).all()
+    for b in range(B):
+        err = max_rel_err(got[b], want[b])
+        assert err < 1e-2, (b, err)
+
+
+# ------------------------------------------------------------------------------------------ standalone cache
+CACHE_CASES = [
+    # P, S_frames, W_frames, heads, chunk sizes in frames (advance flag per chunk: True unless negative)
+    (6, 1, 2, 1, [1, 1, 1, 1, 1, 1]),
+    (15, 1, 6, 2, [3, 3, 3, 3, 3]),        # first chunk straddles sink and ring; third wraps mid-append
+    (70, 0, 3, 1, [1, 2, 3, 1, 2]),        # no sink, tiles of 64 tokens with ragged tails
+    (8, 2, 4, 3, [1, 1, 2, -2, 4, -4, 1]), # negative: same size again with advance = 0
+]
+
+
+@pytest.mark.parametrize("P,Sf,Wf,H,sizes", CACHE_CASES)
+def test_append_evict_is_bit_exact(P, Sf, Wf, H, sizes):
+    D = 128
+    Cw = H * D
+    S, W = Sf * P, Wf * P
+    ccfg = binding.cache_cfg(2, 2, H, P, S, W)
+    storage = torch.full((binding.kv_cache_bytes(ccfg),), 0xFF, dtype=torch.uint8, device=DEV)
+    h = binding.kv_cache_init(ccfg, storage)
+    layer, stream = 1, 1
+    oc = oracle.RollingKVCache(S, W, P, Cw)
+    for i, frames in enumerate(sizes):
+        n = abs(frames) * P
+        k = bf16_randn((n, Cw), 100 + i)
+        v = bf16_randn((n, Cw), 200 + i)
+        binding.kv_cache_append_evict(h, layer, stream, k.to(DEV), v.to(DEV), advance=frames > 0)
+        oc.append_evict(f64(k), f64(v), advance=frames > 0)
+        torch.cuda.synchronize()
+        assert binding.kv_cache_state(h, layer, stream) == oc.state()
+        want_map = oc.slot_map()
+        assert binding.kv_cache_slot_map(h, layer, stream, S + W) == want_map.tolist()
+        kp, vp, ip, cap = binding.kv_cache_device_ptrs(h, layer, stream)
+        base = storage.data_ptr()
+        nb = H * cap * D * 2
+        K = storage[kp - base:kp - base + nb].view(torch.bfloat16).view(H, cap, D).permute(1, 0, 2).reshape(cap, Cw)
+        V = storage[vp - base:vp - base + nb].view(torch.bfloat16).view(H, D, cap).permute(2, 0, 1).reshape(cap, Cw)
+        ids = storage[ip - base:ip - base + cap * 8].view(torch.int64).cpu().numpy()
+        live = want_map >= 0
+        assert np.array_equal(ids[:S + W][live], want_map[live])
+        ko, vo = oc.slot_contents()
+        assert np.array_equal(f64(K)[:S + W][live], ko[live])          # copies: exact
+        assert np.array_equal(f64(V)[:S + W][live], vo[live])
+        # slots never written keep the poison
+        assert torch.isnan(K[:S + W][torch.from_numpy(~live)].float()).all()
+    # the other (layer, stream) pairs were not touched
+    assert binding.kv_cache_state(h, 0, 0)["total"] == 0 and binding.kv_cache_state(h, 1, 0)["total"] == 0
+    binding.kv_cache_reset(h, stream)
+    assert binding.kv_cache_state(h, layer, stream)["total"] == 0
+    binding.kv_cache_destroy(h)
+
+
+def test_append_evict_errors_leave_state_untouched():
+    P, H = 4, 1
+    ccfg = binding.cache_cfg(1, 1, H, P, 4, 8)
+    storage = torch.zeros(binding.kv_cache_bytes(ccfg), dtype=torch.uint8, device=DEV)
+    h = binding.kv_cache_init(ccfg, storage)
+    k = torch.zeros(4, 128, dtype=torch.bfloat16, device=DEV)
+    binding.kv_cache_append_evict(h, 0, 0, k, k)
+    before = binding.kv_cache_state(h, 0, 0)
+    for bad_n, adv, code in ((12, True, binding.INVALID_ARG), (6, True, binding.INVALID_ARG), (8, False, binding.BAD_STATE)):
+        kk = torch.zeros(bad_n, 128, dtype=torch.bfloat16, device=DEV)
+        with pytest.raises(binding.Sdv2Error) as e:
+            binding.kv_cache_append_evict(h, 0, 0, kk, kk, advance=adv)
+        assert e.value.code == code
+        assert binding.kv_cache_state(h, 0, 0) == before
+    with pytest.raises(binding.Sdv2Error):
+        binding.kv_cache_append_evict(h, 1, 0, k, k)
+    binding.kv_cache_destroy(h)

@@ -1,0 +1,94 @@
+"""Host-side checks that need no GPU: the built library loads, exports every symbol the header
+declares, sizes its buffers as documented and rejects bad arguments before touching anything."""
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_07399_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "sdv2.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sdv2_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 20
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.sdv2_version() >= 1
+
+
+def test_struct_sizes_match_the_header_layout():
+    assert C.sizeof(binding.ModelCfg) == 44
+    assert C.sizeof(binding.CacheCfg) == 28
+    assert C.sizeof(binding.ChunkDesc) == 16
+    assert C.sizeof(binding.CacheState) == 32
+    assert C.sizeof(binding.BlockWeights) == 8 + 23 * 8
+    assert C.sizeof(binding.ModelWeights) == 8 + 7 * 8
+
+
+def test_cache_bytes_formula(lib):
+    # per (layer, stream): K and V^T of n_heads * cap * 128 bf16 each, plus cap int64 ids; cap = 64-aligned S+W
+    cfg = binding.cache_cfg(30, 1, 12, 1024, 1024, 2048)
+    cap = 3072
+    assert binding.kv_cache_bytes(cfg) == 30 * (2 * 12 * cap * 128 * 2 + cap * 8)
+    cfg = binding.cache_cfg(2, 4, 40, 1560, 1560, 9360)
+    cap = 10944                                   # 10920 rounded up to 64
+    assert binding.kv_cache_bytes(cfg) == 8 * (2 * 40 * cap * 128 * 2 + cap * 8)
+
+
+@pytest.mark.parametrize("args", [
+    (1, 1, 1, 4, -4, 8),      # negative sink
+    (1, 1, 1, 4, 4, 0),       # empty window
+    (1, 1, 1, 4, 6, 8),       # sink not whole frames
+    (1, 1, 1, 4, 4, 10),      # window not whole frames
+    (0, 1, 1, 4, 4, 8),       # no layers
+])
+def test_cache_cfg_errors(lib, args):
+    with pytest.raises(binding.Sdv2Error) as e:
+        binding.kv_cache_bytes(binding.cache_cfg(*args))
+    assert e.value.code == binding.INVALID_ARG
+
+
+def test_empty_cache_state_and_init_errors(lib):
+    cfg = binding.cache_cfg(2, 3, 1, 4, 4, 8)
+    need = lib.sdv2_kv_cache_bytes(C.byref(cfg))
+    h = C.c_void_p()
+    fake = C.c_void_p(0x10000)                    # never dereferenced: init launches nothing
+    assert lib.sdv2_kv_cache_init(C.byref(cfg), fake, need - 1, C.byref(h)) == binding.INVALID_ARG
+    assert lib.sdv2_kv_cache_init(C.byref(cfg), None, need, C.byref(h)) == binding.INVALID_ARG
+    assert lib.sdv2_kv_cache_init(C.byref(cfg), C.c_void_p(0x10010), need, C.byref(h)) == binding.INVALID_ARG
+    assert lib.sdv2_kv_cache_init(C.byref(cfg), fake, need, C.byref(h)) == binding.OK
+    st = binding.kv_cache_state(h, 1, 2)
+    assert st == {"total": 0, "sink_fill": 0, "win_fill": 0, "oldest_slot": -1, "next_slot": 0, "evicted": 0}
+    assert binding.kv_cache_slot_map(h, 1, 2, 12) == [-1] * 12
+    with pytest.raises(binding.Sdv2Error):
+        binding.kv_cache_state(h, 2, 0)
+    with pytest.raises(binding.Sdv2Error):
+        binding.kv_cache_state(h, 0, 3)
+    binding.kv_cache_destroy(h)
+
+
+def test_workspace_sizes_and_model_cfg_errors(lib):
+    cfg = binding.model_cfg(1536, 12, 8960, 32, 32, 512, 30)
+    rows, Cw, F = 1024, 1536, 8960
+    # h, qkv, q, o, u in bf16 at least
+    assert binding.block_workspace_bytes(cfg, 1, 1024) >= rows * (6 * Cw + F) * 2
+    assert binding.denoise_workspace_bytes(cfg, 1, 1024) > binding.block_workspace_bytes(cfg, 1, 1024)
+    assert binding.text_kv_bytes(cfg) == 512 * 1536 * 2
+    bad = binding.model_cfg(1500, 12, 8960, 32, 32, 512, 30)
+    assert binding.block_workspace_bytes(bad, 1, 1024) == 0
+    assert binding.block_workspace_bytes(cfg, 9, 1024) == 0          # more streams than SDV2_MAX_BATCH
