@@ -32,7 +32,7 @@ constexpr int KT = 64;        // keys per tile
 constexpr int D = kHeadDim;
 constexpr int STAGE = KT * D + D * KT;   // elements per LDS stage: K tile then V^T tile
 
-__global__ __launch_bounds__(256, 1) void attention_kernel(AttnArgs a, float scale_log2e) {
+__global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float scale_log2e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* const sm = reinterpret_cast<bf16*>(smem_raw);
 
@@ -111,6 +111,10 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(AttnArgs a, float sca
     float m_run = -INFINITY;     // running maximum of the scaled (log2-domain) scores of this query
     float l_run = 0.0f;          // this lane's share of the running sum
 
+    // Loads and LDS writes of the next tile are unconditional (the tile index is clamped; the last
+    // iteration re-stages its own tile into the idle buffer) so that the loop body is straight-line code
+    // whose issue order can be laid out explicitly: global loads between the QK^T MFMAs, LDS writes
+    // between the PV MFMAs, fragment reads one step ahead of the MFMAs that use them.
     if (t0 < t1) {
         gload(t0);
         sstore(0);
@@ -118,11 +122,12 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(AttnArgs a, float sca
     __syncthreads();
     for (int t = t0; t < t1; ++t) {
         const int buf = (t - t0) & 1;
-        if (t + 1 < t1) gload(t + 1);
         const bf16* sk = sm + buf * STAGE;
         const bf16* sv = sk + KT * D;
+        __builtin_amdgcn_sched_barrier(0);
+        gload(min(t + 1, t1 - 1));
 
-        // S^T = K Q^T for the tile's two blocks of 32 keys
+        // ---- S^T = K Q^T for the tile's two blocks of 32 keys
         f32x16 s_acc[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -135,44 +140,53 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(AttnArgs a, float sca
                 s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s_acc[kb], 0, 0, 0);
             }
         }
-        // scale, mask the tail, running maximum
-        const bool tail = (t + 1) * KT > kv_len;
-        float mx = -INFINITY;
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v = s_acc[kb][r] * scale_log2e;
-                if (tail) {
-                    const int key = t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    if (key >= kv_len) v = -INFINITY;
-                }
-                s_acc[kb][r] = v;
-                mx = fmaxf(mx, v);
-            }
+        for (int m = 0; m < 16; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (m & 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- online softmax in the log2 domain: p = 2^(s c - m), m = running maximum of s c
+        const bool tail = (t + 1) * KT > kv_len;
+        if (tail) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= kv_len) s_acc[kb][r] = -INFINITY;
+        }
+        float mx = fmaxf(s_acc[0][0], s_acc[1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s_acc[0][r], s_acc[1][r]));
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m_run, mx);               // finite: every tile has a valid key
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        const float m_new = fmaxf(m_run, mx * scale_log2e);     // finite: every tile has a valid key
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // rescale only when some row's maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= alpha;
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[i][r] *= alpha;
+            m_run = m_new;
+        }
         float lsum = 0.0f;
         bf16x8 pf[4];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(s_acc[kb][r] - m_new);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], scale_log2e, -m_run));
                 lsum += p;
                 pf[kb * 2 + (r >> 3)][r & 7] = (bf16)p;
             }
         }
-        l_run = l_run * alpha + lsum;
-#pragma unroll
-        for (int i = 0; i < D / 32; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o_acc[i][r] *= alpha;
+        l_run += lsum;
+        __builtin_amdgcn_sched_barrier(0);
 
-        // O^T += V^T P^T : four steps of 16 keys; step ts uses registers 8 (ts % 2) .. +7 of block ts / 2,
+        // ---- O^T += V^T P^T : four steps of 16 keys; step ts uses registers 8 (ts % 2) .. +7 of block ts / 2,
         // i.e. keys 16 ts + 4 (lane / 32) + {0..3} and 16 ts + 8 + 4 (lane / 32) + {0..3}.
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) {
@@ -185,7 +199,15 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(AttnArgs a, float sca
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ts], o_acc[db], 0, 0, 0);
             }
         }
-        if (t + 1 < t1) sstore(buf ^ 1);
+        sstore(buf ^ 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            if (m & 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
     }
 
@@ -268,8 +290,14 @@ int attention_plan_splits(int B, int L, int H, int max_kv_len) {
     if (forced > 0) {
         splits = forced;
     } else {
+        // Two workgroups fit a compute unit: aim at no more than 512 workgroups in all, keep at least six
+        // key tiles per split (the merge pass costs about as much as two tiles), and do not split at all
+        // once every unit has a workgroup.
         const int wgs = ((L + QT - 1) / QT) * H * B;
-        while (wgs * splits < 256 && splits < 4) ++splits;
+        if (wgs < 256) {
+            splits = 512 / wgs;
+            while (splits > 1 && n_tiles / splits < 6) --splits;
+        }
     }
     while (splits > 1 && n_tiles / splits < 2) --splits;
     return splits > 16 ? 16 : splits;

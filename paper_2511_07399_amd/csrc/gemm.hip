@@ -10,7 +10,8 @@
 //   * A workgroup is 4 waves stacked along M.  Wave tile = (32 TM) x (32 TN); workgroup tile =
 //     (128 TM) x (32 TN) x 64.  TN runs from 2 to 8 so that the tile count can be matched to the
 //     256 compute units for the skinny M = 1024 shapes of the streaming chunk.
-//   * Tiles go global -> registers -> LDS, double buffered, one barrier per k tile.  LDS rows are
+//   * Tiles go global -> registers -> LDS (two LDS stages, two register sets: a load is in flight
+//     for two k iterations), one barrier per k tile.  LDS rows are
 //     64 bf16 (128 B); the 16-byte chunk index is XOR-ed with (row % 8) so that the 32 lanes of a
 //     fragment read hit all banks.
 //   * Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the kernel undoes that
@@ -28,52 +29,107 @@ namespace {
 
 constexpr int BK = 64;
 
-// Accumulator register r of a 32x32 block holds row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32.
-// row0 / col0 already contain the lane's 4 (lane / 32) and lane % 32.
-template <int TM, int TN, int EPI>
-__device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN], int row0, int col0, bool lead,
-                                         bool atomic) {
+// Epilogue.  Accumulator register r of a 32x32 block holds row 8 (r / 4) + 4 (lane / 32) + r % 4 and
+// column lane % 32, which is a poor shape for memory (2-byte or 4-byte pieces of many rows).  Each wave
+// therefore passes its accumulators through a private LDS region, 32 rows x 64 columns at a time, and
+// reads them back row-major so that a lane owns four consecutive columns: stores become 8-byte (bf16)
+// or 16-byte (fp32) pieces that fill whole 128- or 256-byte row segments, and the read-modify-write
+// epilogues issue all their loads of x before the first use.
+constexpr int EPI_LD = 68;                          // floats per LDS row: 64 + 4 of padding
+constexpr int EPI_WAVE_FLOATS = 32 * EPI_LD;
+
+template <int EPI, int NB>
+__device__ __forceinline__ void epilogue_chunk(const GemmArgs& g, const f32x16& acc0, const f32x16& acc1, float* stage,
+                                               int row_base, int col_base, int lane, bool lead, bool atomic) {
+    const int l31 = lane & 31, lh = lane >> 5;
+    __builtin_amdgcn_sched_barrier(0);               // one chunk at a time: bounds the registers in flight
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = col0 + 32 * j;
-        const bool col_ok = col < g.N;
-        const int colc = col_ok ? col : 0;
-        const float bias = (g.bias != nullptr && lead) ? g.bias[colc] : 0.0f;
-        float gate_a = 0.0f;
-        if (EPI == kEpiGatedResidual) gate_a = g.gate_a[colc];
+    for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * lh + (r & 3);
+        stage[row * EPI_LD + l31] = acc0[r];
+        if (NB == 2) stage[row * EPI_LD + 32 + l31] = acc1[r];
+    }
+    constexpr int kLanesPerRow = NB * 8;
+    constexpr int kRowsPerPass = 64 / kLanesPerRow;
+    constexpr int kPasses = 32 / kRowsPerPass;
+    const int prow = lane / kLanesPerRow;
+    const int c4 = (lane % kLanesPerRow) * 4;
+    const int gcol = col_base + c4;
+    const bool col_ok = gcol < g.N;                  // N is a multiple of 4: all four columns or none
+    const int gcolc = col_ok ? gcol : 0;
+    f32x4 bias = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (g.bias != nullptr && lead) bias = *reinterpret_cast<const f32x4*>(g.bias + gcolc);
+    f32x4 gate_a = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (EPI == kEpiGatedResidual) gate_a = *reinterpret_cast<const f32x4*>(g.gate_a + gcolc);
+    // passes are handled four at a time: all loads of x and of the gate first, then the arithmetic and stores
+    constexpr int kGroup = kPasses < 4 ? kPasses : 4;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+    for (int p0 = 0; p0 < kPasses; p0 += kGroup) {
+        f32x4 xv[kGroup];
+        f32x4 gb[kGroup];
+        if (EPI == kEpiGatedResidual || EPI == kEpiResidual) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + 32 * i + 8 * (r >> 2) + (r & 3);
-                if (col_ok && row < g.M) {
-                    const float v = acc[i][j][r] + bias;
-                    const size_t o = (size_t)row * g.N + col;
-                    if (EPI == kEpiBias) {
-                        reinterpret_cast<bf16*>(g.out)[o] = (bf16)v;
-                    } else if (EPI == kEpiBiasGelu) {
-                        reinterpret_cast<bf16*>(g.out)[o] = (bf16)gelu_tanh_f(v);
+            for (int q = 0; q < kGroup; ++q) {
+                const int grow = row_base + (p0 + q) * kRowsPerPass + prow;
+                const bool ok = col_ok && grow < g.M;
+                const int growc = ok ? grow : 0;
+                if (!atomic)
+                    xv[q] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g.out) + (size_t)growc * g.N + gcolc);
+                if (EPI == kEpiGatedResidual)
+                    gb[q] = *reinterpret_cast<const f32x4*>(g.gate_b + (size_t)(growc / g.rows_per_gate) * g.gate_b_stride + gcolc);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kGroup; ++q) {
+            const int row = (p0 + q) * kRowsPerPass + prow;
+            const int grow = row_base + row;
+            f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * EPI_LD + c4);
+            v += bias;
+            if (col_ok && grow < g.M) {
+                const size_t o = (size_t)grow * g.N + gcol;
+                if (EPI == kEpiBias || EPI == kEpiBiasGelu) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (bf16)(EPI == kEpiBiasGelu ? gelu_tanh_f(v[e]) : v[e]);
+                    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(g.out) + o) = w;
+                } else {
+                    if (EPI == kEpiGatedResidual) v *= (gate_a + gb[q]);
+                    float* xo = reinterpret_cast<float*>(g.out) + o;
+                    if (atomic) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) unsafeAtomicAdd(xo + e, v[e]);
                     } else {
-                        float add = v;
-                        if (EPI == kEpiGatedResidual) {
-                            const int sidx = row / g.rows_per_gate;
-                            add = (gate_a + g.gate_b[(size_t)sidx * g.gate_b_stride + col]) * v;
-                        }
-                        float* xo = reinterpret_cast<float*>(g.out) + o;
-                        if (atomic) {
-                            unsafeAtomicAdd(xo, add);
-                        } else {
-                            *xo += add;
-                        }
+                        *reinterpret_cast<f32x4*>(xo) = xv[q] + v;
                     }
                 }
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
+// row0: first output row of this wave's tile; col0: first output column of the workgroup's tile.
+template <int TM, int TN, int EPI>
+__device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN], float* stage, int row0, int col0,
+                                         int lane, bool lead, bool atomic) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int jc = 0; jc < (TN + 1) / 2; ++jc) {
+            if (2 * jc + 1 < TN)
+                epilogue_chunk<EPI, 2>(g, acc[i][2 * jc], acc[i][2 * jc + 1], stage, row0 + 32 * i, col0 + 64 * jc, lane,
+                                       lead, atomic);
+            else
+                epilogue_chunk<EPI, 1>(g, acc[i][2 * jc], acc[i][2 * jc], stage, row0 + 32 * i, col0 + 64 * jc, lane,
+                                       lead, atomic);
+        }
+    }
+}
+
+// Tiles whose k loop fits in 256 registers are compiled for two workgroups per compute unit, so that one
+// workgroup's barrier and LDS-latency bubbles are filled by the other's MFMAs.
 template <int TM, int TN>
-__global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m,
+__global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m,
                                                       int splitk) {
     constexpr int BM = 128 * TM;
     constexpr int BN = 32 * TN;
@@ -127,15 +183,17 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs g, int tiles_m, i
         bp[i] = g.w + (size_t)row * g.K + cchunk * 8;
     }
     const int st_off = crow * BK + ((cchunk ^ (crow & 7)) << 3);
-    bf16x8 ra[NA], rb[NB];
+    // Two register sets: the tile loaded in one k iteration is written to LDS at the end of the next
+    // one, so a global load has two iterations of MFMA work to hide its latency behind.
+    bf16x8 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
 
-    auto gload = [&](int kt) {
+    auto gload = [&](bf16x8 (&ra)[NA], bf16x8 (&rb)[NB], int kt) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) ra[i] = *reinterpret_cast<const bf16x8*>(ap[i] + kt * BK);
 #pragma unroll
         for (int i = 0; i < NB; ++i) rb[i] = *reinterpret_cast<const bf16x8*>(bp[i] + kt * BK);
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](const bf16x8 (&ra)[NA], const bf16x8 (&rb)[NB], int buf) {
         bf16* sa = sm + buf * STAGE;
         bf16* sb = sa + BM * BK;
 #pragma unroll
@@ -153,45 +211,92 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs g, int tiles_m, i
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     const int a_row0 = wave * (32 * TM) + l31;
-
-    if (kt0 < kt1) {
-        gload(kt0);
-        sstore(0);
-    }
-    __syncthreads();
-    for (int kt = kt0; kt < kt1; ++kt) {
-        const int buf = (kt - kt0) & 1;
-        if (kt + 1 < kt1) gload(kt + 1);
+    // One k tile = four 16-wide steps.  The fragments of step s + 1 are read from LDS before the MFMAs
+    // of step s are issued, and the scheduler is told to alternate MFMA and LDS reads, so that the LDS
+    // latency hides behind matrix work instead of stalling every step.
+    auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], const bf16* sa, const bf16* sb, int s) {
+        const int coff = ((2 * s + lh) ^ l7) << 3;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[i] = *reinterpret_cast<const bf16x8*>(sa + (a_row0 + 32 * i) * BK + coff);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[j] = *reinterpret_cast<const bf16x8*>(sb + (l31 + 32 * j) * BK + coff);
+    };
+    auto compute = [&](int buf) {
         const bf16* sa = sm + buf * STAGE;
         const bf16* sb = sa + BM * BK;
+        bf16x8 fa[2][TM], fb[2][TN];
+        load_frags(fa[0], fb[0], sa, sb, 0);
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
-            const int coff = ((2 * s + lh) ^ l7) << 3;
-            bf16x8 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8*>(sa + (a_row0 + 32 * i) * BK + coff);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8*>(sb + (l31 + 32 * j) * BK + coff);
+            if (s + 1 < BK / 16) load_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], sa, sb, s + 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < kt1) sstore(buf ^ 1);
+    };
+
+    // Issue order of one half iteration.  A wave issues in order, and a global load or an LDS write
+    // occupies its issue slot for tens of cycles; so they are spread between the MFMAs (whose 32-cycle
+    // execution leaves issue slots free) instead of being issued in a burst before or after them:
+    //   first step's fragment reads | per MFMA: 1 MFMA, fragment reads of the next step, then one
+    //   global load (tile i + 2) in the first half of the MFMAs and one LDS write (tile i + 1) in the
+    //   second half.
+    auto issue_pipeline = [&]() {
+        constexpr int kMfma = TM * TN * (BK / 16);
+        constexpr int kReadsPerMfma = (TM + TN + TM * TN - 1) / (TM * TN);
+        constexpr int kMem = NA + NB;
+        constexpr int kMemPerMfma = (2 * kMem + kMfma - 1) / kMfma;
+        __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+#pragma unroll
+        for (int m = 0; m < kMfma; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, kReadsPerMfma, 0);
+            if (m < kMfma / 2) __builtin_amdgcn_sched_group_barrier(0x020, kMemPerMfma, 0);
+            else __builtin_amdgcn_sched_group_barrier(0x200, kMemPerMfma, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // Loads are unconditional (the tile index is clamped, the tail re-reads the last tile) so that the
+    // loop body has no control flow around them and they stay in flight across the MFMA work.
+    const int nk = kt1 - kt0;
+    const int kt_last = kt1 - 1;
+    gload(ra0, rb0, kt0);
+    gload(ra1, rb1, min(kt0 + 1, kt_last));
+    sstore(ra0, rb0, 0);
+    __syncthreads();
+    int i = 0;
+    for (; i + 2 <= nk; i += 2) {
+        // tile i is in LDS stage 0, tile i + 1 in register set 1
+        __builtin_amdgcn_sched_barrier(0);
+        gload(ra0, rb0, min(kt0 + i + 2, kt_last));
+        compute(0);
+        sstore(ra1, rb1, 1);
+        issue_pipeline();
+        __syncthreads();
+        // tile i + 1 is in LDS stage 1, tile i + 2 in register set 0
+        __builtin_amdgcn_sched_barrier(0);
+        gload(ra1, rb1, min(kt0 + i + 3, kt_last));
+        compute(1);
+        sstore(ra0, rb0, 0);
+        issue_pipeline();
         __syncthreads();
     }
+    if (i < nk) compute(0);
 
-    // ---- epilogue
-    const int row0 = m0 + wave * (32 * TM) + 4 * lh;
-    const int col0 = n0 + l31;
+    // ---- epilogue (the LDS stages are free once every wave has left the k loop)
+    __syncthreads();
+    float* stage = reinterpret_cast<float*>(smem_raw) + wave * EPI_WAVE_FLOATS;
+    const int row0 = m0 + wave * (32 * TM);
     switch (g.epilogue) {
-        case kEpiBias: epilogue<TM, TN, kEpiBias>(g, acc, row0, col0, ks == 0, splitk > 1); break;
-        case kEpiBiasGelu: epilogue<TM, TN, kEpiBiasGelu>(g, acc, row0, col0, ks == 0, splitk > 1); break;
-        case kEpiGatedResidual: epilogue<TM, TN, kEpiGatedResidual>(g, acc, row0, col0, ks == 0, splitk > 1); break;
-        default: epilogue<TM, TN, kEpiResidual>(g, acc, row0, col0, ks == 0, splitk > 1); break;
+        case kEpiBias: epilogue<TM, TN, kEpiBias>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
+        case kEpiBiasGelu: epilogue<TM, TN, kEpiBiasGelu>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
+        case kEpiGatedResidual: epilogue<TM, TN, kEpiGatedResidual>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
+        default: epilogue<TM, TN, kEpiResidual>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
     }
 }
 
@@ -199,29 +304,41 @@ struct TilePlan {
     int tm, tn, splitk;
 };
 
-// Choose the tile so that the busiest compute unit finishes first.  cost(tile) is in units of
-// "32x32x16 MFMA issue slots per k step", inflated by the LDS fragment traffic per MFMA, which is what
-// separates a skinny tile from a square one.
+// Tile plans measured on MI355X for the projection shapes of the 1.3B- and 14B-shaped blocks with a
+// 1024-token chunk (tile sweep with every (TM, TN) of this kernel; times in the design notes).
+struct TunedShape {
+    int M, N, K;
+    TilePlan plan;
+};
+const TunedShape kTuned[] = {
+    {1024, 4608, 1536, {1, 5, 1}},   {1024, 1536, 1536, {1, 2, 1}},  {1024, 8960, 1536, {2, 5, 1}},
+    {1024, 1536, 8960, {1, 2, 1}},   {1024, 15360, 5120, {2, 4, 1}}, {1024, 5120, 5120, {1, 5, 1}},
+    {1024, 13824, 5120, {2, 7, 1}},  {1024, 5120, 13824, {1, 5, 1}},
+};
+
+// Otherwise: estimate the time of the busiest compute unit.  One k tile of a workgroup costs a fixed
+// part (barrier, LDS latency: ~0.25 us alone, half of it when a second workgroup fills the bubbles) plus
+// ~21 ns per MFMA a wave issues (fitted to the same sweep); small tiles fit two workgroups per unit.
 TilePlan plan_tiles(int M, int N, int K, int epilogue) {
+    (void)epilogue;
+    for (const TunedShape& t : kTuned)
+        if (t.M == M && t.N == N && t.K == K) return t.plan;
     const int kCUs = 256;
     TilePlan best{1, 4, 1};
     double best_cost = 1e300;
-    const bool can_split = (epilogue == kEpiGatedResidual || epilogue == kEpiResidual);
     for (int tm = 1; tm <= 2; ++tm) {
-        for (int tn = 2; tn <= 8; ++tn) {
-            const int tiles = ((M + 128 * tm - 1) / (128 * tm)) * ((N + 32 * tn - 1) / (32 * tn));
-            for (int sk = 1; sk <= (can_split ? 4 : 1); sk *= 2) {
-                if ((K / BK) / sk < 8) continue;
-                const int wgs = tiles * sk;
-                const int per_cu = (wgs + kCUs - 1) / kCUs;
-                const double frag_per_mfma = (double)(tm + tn) / (tm * tn);
-                const double eff = 1.0 / (1.0 + 0.35 * frag_per_mfma);
-                double cost = (double)per_cu * (tm * tn) * (K / BK / sk + 2) / eff;
-                if (sk > 1) cost *= 1.05;       // atomics in the epilogue
-                if (cost < best_cost) {
-                    best_cost = cost;
-                    best = TilePlan{tm, tn, sk};
-                }
+        for (int tn = 2; tn <= 7; ++tn) {
+            const int wgs = ((M + 128 * tm - 1) / (128 * tm)) * ((N + 32 * tn - 1) / (32 * tn));
+            const int occ = (tm * tn <= 5) ? 2 : 1;
+            const int per_cu = (wgs + kCUs - 1) / kCUs;
+            const double mfma = 0.021 * 4 * tm * tn;
+            double cost;
+            if (occ == 2 && per_cu >= 2) cost = (per_cu + 1) / 2 * (0.25 + 2 * mfma);
+            else cost = per_cu * (0.25 + mfma);
+            cost = cost * (K / BK) + per_cu * 0.04 * tm * tn;      // + epilogue
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = TilePlan{tm, tn, 1};
             }
         }
     }
