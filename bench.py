@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--workload", default="wan1.3b-step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="blocks the oracle times (0: all, bounded to ~30 s)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run a plain device copy of this many MiB (read + write) three times before the timed "
+                         "region, as the known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -58,6 +61,14 @@ def main():
     n_inputs = 8
     xs = [torch.stack([wk.chunk_input(wl, c, s, device=dev) for s in range(B)]).contiguous() for c in range(n_inputs)]
     stream = torch.cuda.current_stream()
+
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration * (1 << 20) // 4, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # fill the caches so that the timed steps run at steady state (every chunk evicts)
     fill_chunks = (wl.sink_frames + wl.window_frames + frames - 1) // frames + 1
@@ -139,7 +150,7 @@ def main():
         "bound": "mfma", "kernel": "gemm_kernel @ FFN-1 (M=%d, N=%d, K=%d, bf16)" % (rows, wl.F, Cw),
         "achieved": round(achieved, 1), "peak": cm.MI355X_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
         "frac": round(achieved * 1e12 / cm.MI355X_BF16_FLOPS, 4), "avg_launch_us": round(dom_us, 2),
-        "flops_per_launch": flops[dom], "traffic": None,
+        "flops_per_launch": flops[dom], "traffic": load_traffic(wl.name, "FFN-1 gemm"),
     }
     step_flops = wl.N * cm.block_flops(rows, Cw, wl.F, l_kv, wl.L_t)
 
@@ -166,6 +177,17 @@ def main():
     }
     gpu.close()
     print(json.dumps(out))
+
+
+def load_traffic(workload, launch_site):
+    """HBM bytes per launch of the dominant kernel, as derived from the rocprofv3 --pmc runs whose summary
+    is committed under profiles/ (null when no such measurement is recorded for this workload)."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(launch_site)
+    except (OSError, ValueError):
+        return None
 
 
 def time_oracle(wl, n_layers_req):
