@@ -16,7 +16,10 @@
 //     trip for P.
 //   * That needs V^T tiles with keys contiguous, which is why the cache stores values transposed
 //     ([head][128][cap]); K tiles are contiguous 16 KB blocks of the [head][cap][128] key cache.
-//   * K and V^T tiles of 64 keys go global -> registers -> LDS, double buffered, XOR-swizzled rows.
+//   * K and V^T tiles of 64 keys go global -> registers -> LDS, double buffered.  Rows are swizzled for
+//     the 64-bank LDS: K rows (256 B) XOR the 16-byte chunk index with row % 16; V^T rows (128 B) XOR it
+//     with (row / 2) % 8 and swap the two 8-byte halves of a chunk in rows 16..31 of each block of 32, so
+//     that the 32 lanes of an 8-byte fragment read hit 32 different bank groups.
 //   * Skinny launches (few query tiles x heads) split the key range over several workgroups, which
 //     write normalised partial outputs with their (max, sum); a small kernel merges them.
 #include "common.h"
@@ -41,7 +44,6 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
     const int wave = tid >> 6;
     const int l31 = lane & 31;
     const int lh = lane >> 5;
-    const int l7 = lane & 7;
 
     const int qt = blockIdx.x;
     const int h = blockIdx.y;
@@ -93,13 +95,15 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         for (int i = 0; i < 4; ++i) {
             const int idx = tid + 256 * i;
             const int row = idx >> 4, c = idx & 15;
-            *reinterpret_cast<bf16x8*>(sk + row * D + ((c ^ (row & 7)) << 3)) = rk[i];
+            *reinterpret_cast<bf16x8*>(sk + row * D + ((c ^ (row & 15)) << 3)) = rk[i];
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int idx = tid + 256 * i;
             const int row = idx >> 3, c = idx & 7;
-            *reinterpret_cast<bf16x8*>(sv + row * KT + ((c ^ (row & 7)) << 3)) = rv[i];
+            bf16x8 w = rv[i];
+            if (row & 16) w = __builtin_shufflevector(w, w, 4, 5, 6, 7, 0, 1, 2, 3);
+            *reinterpret_cast<bf16x8*>(sv + row * KT + ((c ^ ((row >> 1) & 7)) << 3)) = w;
         }
     };
 
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
 #pragma unroll
             for (int s = 0; s < D / 16; ++s) {
                 const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + l31) * D +
-                                                                    (((2 * s + lh) ^ l7) << 3));
+                                                                    (((2 * s + lh) ^ (l31 & 15)) << 3));
                 s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s_acc[kb], 0, 0, 0);
             }
         }
@@ -192,9 +196,9 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         for (int ts = 0; ts < 4; ++ts) {
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                const bf16* vrow = sv + (db * 32 + l31) * KT + 4 * lh;
-                const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ts) ^ l7) << 3));
-                const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ts + 1) ^ l7) << 3));
+                const bf16* vrow = sv + (db * 32 + l31) * KT + 4 * (lh ^ (l31 >> 4));
+                const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ts) ^ ((l31 >> 1) & 7)) << 3));
+                const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ts + 1) ^ ((l31 >> 1) & 7)) << 3));
                 const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ts], o_acc[db], 0, 0, 0);
             }

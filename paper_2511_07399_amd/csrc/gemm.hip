@@ -10,15 +10,17 @@
 //   * A workgroup is 4 waves stacked along M.  Wave tile = (32 TM) x (32 TN); workgroup tile =
 //     (128 TM) x (32 TN) x 64.  TN runs from 2 to 8 so that the tile count can be matched to the
 //     256 compute units for the skinny M = 1024 shapes of the streaming chunk.
-//   * Tiles go global -> registers -> LDS (two LDS stages, two register sets: a load is in flight
-//     for two k iterations), one barrier per k tile.  LDS rows are
-//     64 bf16 (128 B); the 16-byte chunk index is XOR-ed with (row % 8) so that the 32 lanes of a
-//     fragment read hit all banks.
+//   * Tiles go global -> registers -> LDS (two LDS stages, two or three register sets: a load is in
+//     flight for two or three k iterations), one barrier per k tile.  LDS rows are 64 bf16 (128 B); the
+//     16-byte chunk index is XOR-ed with (row / 2) % 8 so that fragment reads are conflict free on the
+//     64-bank LDS.
 //   * Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the kernel undoes that
 //     so that each XCD (one L2) owns a contiguous range of tiles, ordered in groups of M tiles that
 //     share weight tiles.
 //   * Optional split-K for the two fp32 read-modify-write epilogues (hardware fp32 atomics on x).
 #include "common.h"
+
+#include <type_traits>
 
 #include <stdio.h>
 #include <stdlib.h>
@@ -26,8 +28,6 @@
 namespace sdv2 {
 
 namespace {
-
-constexpr int BK = 64;
 
 // Epilogue.  Accumulator register r of a 32x32 block holds row 8 (r / 4) + 4 (lane / 32) + r % 4 and
 // column lane % 32, which is a poor shape for memory (2-byte or 4-byte pieces of many rows).  Each wave
@@ -127,16 +127,25 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN
 }
 
 // Tiles whose k loop fits in 256 registers are compiled for two workgroups per compute unit, so that one
-// workgroup's barrier and LDS-latency bubbles are filled by the other's MFMAs.
-template <int TM, int TN>
-__global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m,
-                                                      int splitk) {
+// workgroup's barrier and LDS-latency bubbles are filled by the other's MFMAs.  BK (64 or 128) is the k
+// depth of an LDS stage: a deeper stage halves the number of barriers, which is what the small tiles
+// (few MFMAs per barrier) are short of.
+// PF is the number of register sets = how many k tiles ahead the global loads run.  A compute unit needs
+// on the order of 100 KB of loads in flight to cover the L2 latency; tiles that run one workgroup per
+// unit get there with three sets, small tiles with two sets and two or three workgroups per unit.
+template <int TM, int TN, int BK, int PF>
+__global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1)) void gemm_kernel(GemmArgs g, int tiles_m,
+                                                                                                  int tiles_n, int group_m,
+                                                                                                  int splitk) {
     constexpr int BM = 128 * TM;
     constexpr int BN = 32 * TN;
-    constexpr int NA = 4 * TM;      // 16-byte chunks of the A tile per thread
-    constexpr int NB = TN;          // of the W tile
+    constexpr int CPR = BK / 8;                 // 16-byte chunks per LDS row
+    constexpr int RPP = 256 / CPR;              // tile rows covered by one pass of the 256 threads
+    constexpr int NA = BM / RPP;                // 16-byte chunks of the A tile per thread
+    constexpr int NB = BN / RPP;                // of the W tile
+    constexpr int KS = BK / 16;                 // MFMA k steps per stage
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* const sm = reinterpret_cast<bf16*>(smem_raw);     // [2][BM*64 | BN*64]
+    bf16* const sm = reinterpret_cast<bf16*>(smem_raw);     // [2][BM*BK | BN*BK]
     constexpr int STAGE = (BM + BN) * BK;
 
     const int tid = threadIdx.x;
@@ -144,7 +153,6 @@ __global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmA
     const int wave = tid >> 6;
     const int l31 = lane & 31;
     const int lh = lane >> 5;
-    const int l7 = lane & 7;
 
     // ---- which tile: undo the round-robin XCD dispatch, then grouped ordering
     const int nwg = gridDim.x;                                   // multiple of 8
@@ -168,38 +176,43 @@ __global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmA
     const int kt1 = (int)((long long)(ks + 1) * KT / splitk);
 
     // ---- global -> register staging
-    const int crow = tid >> 3;          // 0..31
-    const int cchunk = tid & 7;
+    const int crow = tid / CPR;
+    const int cchunk = tid % CPR;
     const bf16* ap[NA];
     const bf16* bp[NB];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        const int row = min(m0 + crow + 32 * i, g.M - 1);
+        const int row = min(m0 + crow + RPP * i, g.M - 1);
         ap[i] = g.a + (size_t)row * g.K + cchunk * 8;
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-        const int row = min(n0 + crow + 32 * i, g.N - 1);
+        const int row = min(n0 + crow + RPP * i, g.N - 1);
         bp[i] = g.w + (size_t)row * g.K + cchunk * 8;
     }
-    const int st_off = crow * BK + ((cchunk ^ (crow & 7)) << 3);
-    // Two register sets: the tile loaded in one k iteration is written to LDS at the end of the next
-    // one, so a global load has two iterations of MFMA work to hide its latency behind.
-    bf16x8 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+    // LDS swizzle: the 16-byte chunk c of row r is stored at position c ^ ((r / 2) % 8).  The LDS has 64
+    // banks (256 bytes per clock); a row is 128 bytes, so rows r and r + 1 fall in different bank halves
+    // and the sixteen lanes that a b128 read serves per clock (rows r .. r + 15, same chunk) then hit
+    // sixteen different 16-byte slots.  (XOR with r % 8, the 32-bank recipe, reads at half rate here.)
+    // RPP is a multiple of 16, so ((row / 2) % 8) of every chunk this thread stages is that of crow.
+    const int st_off = crow * BK + ((cchunk ^ ((crow >> 1) & 7)) << 3);
+    // PF register sets: tile t lives in set t % PF from its load until it is written to LDS stage t % 2
+    // at the end of iteration t - 1, so a global load has PF iterations of MFMA work to hide behind.
+    bf16x8 ra[PF][NA], rb[PF][NB];
 
-    auto gload = [&](bf16x8 (&ra)[NA], bf16x8 (&rb)[NB], int kt) {
+    auto gload = [&](bf16x8 (&xa)[NA], bf16x8 (&xb)[NB], int kt) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) ra[i] = *reinterpret_cast<const bf16x8*>(ap[i] + kt * BK);
+        for (int i = 0; i < NA; ++i) xa[i] = *reinterpret_cast<const bf16x8*>(ap[i] + kt * BK);
 #pragma unroll
-        for (int i = 0; i < NB; ++i) rb[i] = *reinterpret_cast<const bf16x8*>(bp[i] + kt * BK);
+        for (int i = 0; i < NB; ++i) xb[i] = *reinterpret_cast<const bf16x8*>(bp[i] + kt * BK);
     };
-    auto sstore = [&](const bf16x8 (&ra)[NA], const bf16x8 (&rb)[NB], int buf) {
+    auto sstore = [&](const bf16x8 (&xa)[NA], const bf16x8 (&xb)[NB], int buf) {
         bf16* sa = sm + buf * STAGE;
         bf16* sb = sa + BM * BK;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<bf16x8*>(sa + st_off + i * 32 * BK) = ra[i];
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<bf16x8*>(sa + st_off + i * RPP * BK) = xa[i];
 #pragma unroll
-        for (int i = 0; i < NB; ++i) *reinterpret_cast<bf16x8*>(sb + st_off + i * 32 * BK) = rb[i];
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<bf16x8*>(sb + st_off + i * RPP * BK) = xb[i];
     };
 
     f32x16 acc[TM][TN];
@@ -211,11 +224,10 @@ __global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmA
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     const int a_row0 = wave * (32 * TM) + l31;
-    // One k tile = four 16-wide steps.  The fragments of step s + 1 are read from LDS before the MFMAs
-    // of step s are issued, and the scheduler is told to alternate MFMA and LDS reads, so that the LDS
-    // latency hides behind matrix work instead of stalling every step.
+    // One stage = KS 16-wide steps.  The fragments of step s + 1 are read from LDS before the MFMAs of
+    // step s are issued, so that the LDS latency hides behind matrix work.
     auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], const bf16* sa, const bf16* sb, int s) {
-        const int coff = ((2 * s + lh) ^ l7) << 3;
+        const int coff = ((2 * s + lh) ^ ((l31 >> 1) & 7)) << 3;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             fa[i] = *reinterpret_cast<const bf16x8*>(sa + (a_row0 + 32 * i) * BK + coff);
@@ -229,8 +241,8 @@ __global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmA
         bf16x8 fa[2][TM], fb[2][TN];
         load_frags(fa[0], fb[0], sa, sb, 0);
 #pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            if (s + 1 < BK / 16) load_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], sa, sb, s + 1);
+        for (int s = 0; s < KS; ++s) {
+            if (s + 1 < KS) load_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], sa, sb, s + 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -246,7 +258,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmA
     //   global load (tile i + 2) in the first half of the MFMAs and one LDS write (tile i + 1) in the
     //   second half.
     auto issue_pipeline = [&]() {
-        constexpr int kMfma = TM * TN * (BK / 16);
+        constexpr int kMfma = TM * TN * KS;
         constexpr int kReadsPerMfma = (TM + TN + TM * TN - 1) / (TM * TN);
         constexpr int kMem = NA + NB;
         constexpr int kMemPerMfma = (2 * kMem + kMfma - 1) / kMfma;
@@ -261,32 +273,47 @@ __global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmA
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // Loads are unconditional (the tile index is clamped, the tail re-reads the last tile) so that the
-    // loop body has no control flow around them and they stay in flight across the MFMA work.
+    // Loads are unconditional (the tile index is clamped, the tail re-reads the last tile) so that a step
+    // has no control flow around them and they stay in flight across the MFMA work.  Step k of the
+    // unrolled body: tile t sits in LDS stage k % 2; load tile t + PF into set k % PF (free since tile t
+    // was written out), compute, write set (k + 1) % PF (tile t + 1) to the other stage.
     const int nk = kt1 - kt0;
     const int kt_last = kt1 - 1;
-    gload(ra0, rb0, kt0);
-    gload(ra1, rb1, min(kt0 + 1, kt_last));
-    sstore(ra0, rb0, 0);
-    __syncthreads();
-    int i = 0;
-    for (; i + 2 <= nk; i += 2) {
-        // tile i is in LDS stage 0, tile i + 1 in register set 1
+    auto step = [&](auto kc, int t) {
+        constexpr int k = decltype(kc)::value;
         __builtin_amdgcn_sched_barrier(0);
-        gload(ra0, rb0, min(kt0 + i + 2, kt_last));
-        compute(0);
-        sstore(ra1, rb1, 1);
+        gload(ra[k % PF], rb[k % PF], min(kt0 + t + PF, kt_last));
+        compute(k % 2);
+        sstore(ra[(k + 1) % PF], rb[(k + 1) % PF], (k + 1) % 2);
         issue_pipeline();
         __syncthreads();
-        // tile i + 1 is in LDS stage 1, tile i + 2 in register set 0
-        __builtin_amdgcn_sched_barrier(0);
-        gload(ra1, rb1, min(kt0 + i + 3, kt_last));
-        compute(1);
-        sstore(ra0, rb0, 0);
-        issue_pipeline();
-        __syncthreads();
+    };
+    if (nk > 0) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) gload(ra[p], rb[p], min(kt0 + p, kt_last));
+        sstore(ra[0], rb[0], 0);
     }
-    if (i < nk) compute(0);
+    __syncthreads();
+    constexpr int U = (PF % 2 == 0) ? PF : 2 * PF;      // unroll so that stage and set indices are constants
+    int i = 0;
+    for (; i + U <= nk; i += U) {
+        step(std::integral_constant<int, 0>{}, i);
+        step(std::integral_constant<int, 1>{}, i + 1);
+        if constexpr (U > 2) {
+            step(std::integral_constant<int, 2>{}, i + 2);
+            step(std::integral_constant<int, 3>{}, i + 3);
+            step(std::integral_constant<int, 4>{}, i + 4);
+            step(std::integral_constant<int, 5>{}, i + 5);
+        }
+    }
+    // tail: fewer than U tiles left; the last tile needs no write-out but doing one is harmless
+    if (i < nk) step(std::integral_constant<int, 0>{}, i);
+    if constexpr (U > 2) {
+        if (i + 1 < nk) step(std::integral_constant<int, 1>{}, i + 1);
+        if (i + 2 < nk) step(std::integral_constant<int, 2>{}, i + 2);
+        if (i + 3 < nk) step(std::integral_constant<int, 3>{}, i + 3);
+        if (i + 4 < nk) step(std::integral_constant<int, 4>{}, i + 4);
+    }
 
     // ---- epilogue (the LDS stages are free once every wave has left the k loop)
     __syncthreads();
@@ -301,30 +328,30 @@ __global__ __launch_bounds__(256, (TM * TN <= 5 ? 2 : 1)) void gemm_kernel(GemmA
 }
 
 struct TilePlan {
-    int tm, tn, splitk;
+    int tm, tn, splitk, pf;
 };
 
 // Tile plans measured on MI355X for the projection shapes of the 1.3B- and 14B-shaped blocks with a
-// 1024-token chunk (tile sweep with every (TM, TN) of this kernel; times in the design notes).
+// 1024-token chunk (tile sweep with every (TM, TN, PF) of this kernel).
 struct TunedShape {
     int M, N, K;
     TilePlan plan;
 };
 const TunedShape kTuned[] = {
-    {1024, 4608, 1536, {1, 5, 1}},   {1024, 1536, 1536, {1, 2, 1}},  {1024, 8960, 1536, {2, 5, 1}},
-    {1024, 1536, 8960, {1, 2, 1}},   {1024, 15360, 5120, {2, 4, 1}}, {1024, 5120, 5120, {1, 5, 1}},
-    {1024, 13824, 5120, {2, 7, 1}},  {1024, 5120, 13824, {1, 5, 1}},
+    {1024, 4608, 1536, {1, 5, 1, 2}},   {1024, 1536, 1536, {1, 2, 1, 2}},  {1024, 8960, 1536, {2, 5, 1, 2}},
+    {1024, 1536, 8960, {1, 2, 1, 2}},   {1024, 15360, 5120, {1, 5, 1, 2}}, {1024, 5120, 5120, {1, 5, 1, 2}},
+    {1024, 13824, 5120, {2, 7, 1, 2}},  {1024, 5120, 13824, {1, 5, 1, 2}},
 };
 
 // Otherwise: estimate the time of the busiest compute unit.  One k tile of a workgroup costs a fixed
-// part (barrier, LDS latency: ~0.25 us alone, half of it when a second workgroup fills the bubbles) plus
-// ~21 ns per MFMA a wave issues (fitted to the same sweep); small tiles fit two workgroups per unit.
+// part (~0.25 us alone, half of it when a second workgroup fills the bubbles) plus ~21 ns per MFMA a wave
+// issues (fitted to the same sweep); small tiles fit two workgroups per unit.
 TilePlan plan_tiles(int M, int N, int K, int epilogue) {
     (void)epilogue;
     for (const TunedShape& t : kTuned)
         if (t.M == M && t.N == N && t.K == K) return t.plan;
     const int kCUs = 256;
-    TilePlan best{1, 4, 1};
+    TilePlan best{1, 4, 1, 2};
     double best_cost = 1e300;
     for (int tm = 1; tm <= 2; ++tm) {
         for (int tn = 2; tn <= 7; ++tn) {
@@ -335,74 +362,83 @@ TilePlan plan_tiles(int M, int N, int K, int epilogue) {
             double cost;
             if (occ == 2 && per_cu >= 2) cost = (per_cu + 1) / 2 * (0.25 + 2 * mfma);
             else cost = per_cu * (0.25 + mfma);
-            cost = cost * (K / BK) + per_cu * 0.04 * tm * tn;      // + epilogue
+            cost = cost * (K / 64) + per_cu * 0.04 * tm * tn;      // + epilogue
             if (cost < best_cost) {
                 best_cost = cost;
-                best = TilePlan{tm, tn, 1};
+                best = TilePlan{tm, tn, 1, 2};
             }
         }
     }
     return best;
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int PF>
 hipError_t launch_one(const GemmArgs& g, int splitk, hipStream_t s) {
+    constexpr int BK = 64;
     constexpr int BM = 128 * TM, BN = 32 * TN;
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.N + BN - 1) / BN;
     const int wgs = tiles_m * tiles_n * splitk;
     const int grid = (wgs + 7) / 8 * 8;
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+    static_assert((size_t)2 * (BM + BN) * BK * sizeof(bf16) >= 4 * EPI_WAVE_FLOATS * sizeof(float), "epilogue staging");
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TM, TN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TM, TN, BK, PF>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int group_m = 8;
-    hipLaunchKernelGGL((gemm_kernel<TM, TN>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m,
+    hipLaunchKernelGGL((gemm_kernel<TM, TN, BK, PF>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m,
                        splitk);
     return hipGetLastError();
 }
 
-template <int TM>
+template <int TM, int PF>
 hipError_t launch_tn(const GemmArgs& g, int tn, int splitk, hipStream_t s) {
     switch (tn) {
-        case 2: return launch_one<TM, 2>(g, splitk, s);
-        case 3: return launch_one<TM, 3>(g, splitk, s);
-        case 4: return launch_one<TM, 4>(g, splitk, s);
-        case 5: return launch_one<TM, 5>(g, splitk, s);
-        case 6: return launch_one<TM, 6>(g, splitk, s);
-        case 7: return launch_one<TM, 7>(g, splitk, s);
-        case 8: return launch_one<TM, 8>(g, splitk, s);
+        case 2: return launch_one<TM, 2, PF>(g, splitk, s);
+        case 3: return launch_one<TM, 3, PF>(g, splitk, s);
+        case 4: return launch_one<TM, 4, PF>(g, splitk, s);
+        case 5: return launch_one<TM, 5, PF>(g, splitk, s);
+        case 6: return launch_one<TM, 6, PF>(g, splitk, s);
+    }
+    if constexpr (PF == 2) {
+        switch (tn) {
+            case 7: return launch_one<TM, 7, PF>(g, splitk, s);
+            case 8: return launch_one<TM, 8, PF>(g, splitk, s);
+        }
     }
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-// Environment override for tuning runs and tests: SDV2_GEMM_TILE="tm,tn,splitk" (read at every call).
+// Environment override for tuning runs and tests: SDV2_GEMM_TILE="tm,tn,splitk[,pf]" (read at every call).
 static bool tile_override(TilePlan* p) {
     const char* e = getenv("SDV2_GEMM_TILE");
-    int a, b, c;
-    if (e && sscanf(e, "%d,%d,%d", &a, &b, &c) == 3 && a >= 1 && a <= 2 && b >= 2 && b <= 8 && c >= 1 && c <= 16) {
-        *p = TilePlan{a, b, c};
+    int a, b, c, d = 2;
+    if (e && sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) >= 3 && a >= 1 && a <= 2 && b >= 2 && b <= 8 && c >= 1 && c <= 16 &&
+        (d == 2 || (d == 3 && b <= 6))) {
+        *p = TilePlan{a, b, c, d};
         return true;
     }
     return false;
 }
 
-hipError_t launch_gemm_planned(const GemmArgs& g, int tm, int tn, int splitk, hipStream_t s) {
+hipError_t launch_gemm_planned(const GemmArgs& g, TilePlan p, hipStream_t s) {
+    int splitk = p.splitk;
     if (g.epilogue == kEpiBias || g.epilogue == kEpiBiasGelu) splitk = 1;
-    if (splitk > g.K / BK) splitk = 1;
-    return tm == 1 ? launch_tn<1>(g, tn, splitk, s) : launch_tn<2>(g, tn, splitk, s);
+    if (splitk > g.K / 64) splitk = 1;
+    if (p.pf == 3) return p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
+    return p.tm == 1 ? launch_tn<1, 2>(g, p.tn, splitk, s) : launch_tn<2, 2>(g, p.tn, splitk, s);
 }
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue);
     tile_override(&p);
-    return launch_gemm_planned(g, p.tm, p.tn, p.splitk, s);
+    return launch_gemm_planned(g, p, s);
 }
 
 }  // namespace sdv2

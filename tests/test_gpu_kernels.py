@@ -42,6 +42,10 @@ GEMM_CASES = [
     (300, 512, 1024, 2, "1,4,2"),          # gated residual, split-K atomics, ragged M
     (300, 512, 1024, 2, None),
     (260, 256, 2048, 3, "2,8,4"),          # residual, biggest tile, split-K 4
+    (300, 384, 768, 0, "1,3,1,3"),         # three register sets (loads three k tiles ahead), 12 k tiles
+    (520, 640, 704, 2, "2,5,1,3"),         # three sets, 11 k tiles (tail of the unrolled-by-6 loop)
+    (256, 256, 64, 3, "2,2,1,3"),          # three sets, a single k tile
+    (256, 384, 448, 1, "1,6,1,3"),         # three sets, 7 k tiles
     (1024, 2048, 512, 1, None),            # tiny workload FFN-1
     (1024, 4608, 1536, 0, None),           # 1.3B QKV
     (1024, 1536, 8960, 2, None),           # 1.3B FFN-2 (planner's own tile and split)
