@@ -17,7 +17,9 @@
 //   * Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the kernel undoes that
 //     so that each XCD (one L2) owns a contiguous range of tiles, ordered in groups of M tiles that
 //     share weight tiles.
-//   * Optional split-K for the two fp32 read-modify-write epilogues (hardware fp32 atomics on x).
+//   * The k range is never split over workgroups: fp32 atomics on the output cost ~40 us per 1.5 M elements
+//     here, and a last-arriver reduction through memory needs device-scope fences that write back and
+//     invalidate the whole L2 of an XCD (measured +100 us on a 64 us launch).
 #include "common.h"
 
 #include <type_traits>
@@ -40,7 +42,7 @@ constexpr int EPI_WAVE_FLOATS = 32 * EPI_LD;
 
 template <int EPI, int NB>
 __device__ __forceinline__ void epilogue_chunk(const GemmArgs& g, const f32x16& acc0, const f32x16& acc1, float* stage,
-                                               int row_base, int col_base, int lane, bool lead, bool atomic) {
+                                               int row_base, int col_base, int lane) {
     const int l31 = lane & 31, lh = lane >> 5;
     __builtin_amdgcn_sched_barrier(0);               // one chunk at a time: bounds the registers in flight
 #pragma unroll
@@ -58,7 +60,7 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& g, const f32x16& 
     const bool col_ok = gcol < g.N;                  // N is a multiple of 4: all four columns or none
     const int gcolc = col_ok ? gcol : 0;
     f32x4 bias = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (g.bias != nullptr && lead) bias = *reinterpret_cast<const f32x4*>(g.bias + gcolc);
+    if (g.bias != nullptr) bias = *reinterpret_cast<const f32x4*>(g.bias + gcolc);
     f32x4 gate_a = {0.0f, 0.0f, 0.0f, 0.0f};
     if (EPI == kEpiGatedResidual) gate_a = *reinterpret_cast<const f32x4*>(g.gate_a + gcolc);
     // passes are handled four at a time: all loads of x and of the gate first, then the arithmetic and stores
@@ -73,8 +75,7 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& g, const f32x16& 
                 const int grow = row_base + (p0 + q) * kRowsPerPass + prow;
                 const bool ok = col_ok && grow < g.M;
                 const int growc = ok ? grow : 0;
-                if (!atomic)
-                    xv[q] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g.out) + (size_t)growc * g.N + gcolc);
+                xv[q] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g.out) + (size_t)growc * g.N + gcolc);
                 if (EPI == kEpiGatedResidual)
                     gb[q] = *reinterpret_cast<const f32x4*>(g.gate_b + (size_t)(growc / g.rows_per_gate) * g.gate_b_stride + gcolc);
             }
@@ -94,13 +95,7 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& g, const f32x16& 
                     *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(g.out) + o) = w;
                 } else {
                     if (EPI == kEpiGatedResidual) v *= (gate_a + gb[q]);
-                    float* xo = reinterpret_cast<float*>(g.out) + o;
-                    if (atomic) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) unsafeAtomicAdd(xo + e, v[e]);
-                    } else {
-                        *reinterpret_cast<f32x4*>(xo) = xv[q] + v;
-                    }
+                    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.out) + o) = xv[q] + v;
                 }
             }
         }
@@ -111,18 +106,27 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& g, const f32x16& 
 // row0: first output row of this wave's tile; col0: first output column of the workgroup's tile.
 template <int TM, int TN, int EPI>
 __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN], float* stage, int row0, int col0,
-                                         int lane, bool lead, bool atomic) {
+                                         int lane) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int jc = 0; jc < (TN + 1) / 2; ++jc) {
             if (2 * jc + 1 < TN)
-                epilogue_chunk<EPI, 2>(g, acc[i][2 * jc], acc[i][2 * jc + 1], stage, row0 + 32 * i, col0 + 64 * jc, lane,
-                                       lead, atomic);
+                epilogue_chunk<EPI, 2>(g, acc[i][2 * jc], acc[i][2 * jc + 1], stage, row0 + 32 * i, col0 + 64 * jc, lane);
             else
-                epilogue_chunk<EPI, 1>(g, acc[i][2 * jc], acc[i][2 * jc], stage, row0 + 32 * i, col0 + 64 * jc, lane,
-                                       lead, atomic);
+                epilogue_chunk<EPI, 1>(g, acc[i][2 * jc], acc[i][2 * jc], stage, row0 + 32 * i, col0 + 64 * jc, lane);
         }
+    }
+}
+
+template <int TM, int TN>
+__device__ __forceinline__ void run_epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN], float* stage, int row0, int col0,
+                                             int lane) {
+    switch (g.epilogue) {
+        case kEpiBias: epilogue<TM, TN, kEpiBias>(g, acc, stage, row0, col0, lane); break;
+        case kEpiBiasGelu: epilogue<TM, TN, kEpiBiasGelu>(g, acc, stage, row0, col0, lane); break;
+        case kEpiGatedResidual: epilogue<TM, TN, kEpiGatedResidual>(g, acc, stage, row0, col0, lane); break;
+        default: epilogue<TM, TN, kEpiResidual>(g, acc, stage, row0, col0, lane); break;
     }
 }
 
@@ -135,8 +139,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN
 // unit get there with three sets, small tiles with two sets and two or three workgroups per unit.
 template <int TM, int TN, int BK, int PF>
 __global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1)) void gemm_kernel(GemmArgs g, int tiles_m,
-                                                                                                  int tiles_n, int group_m,
-                                                                                                  int splitk) {
+                                                                                                  int tiles_n, int group_m) {
     constexpr int BM = 128 * TM;
     constexpr int BN = 32 * TN;
     constexpr int CPR = BK / 8;                 // 16-byte chunks per LDS row
@@ -157,10 +160,8 @@ __global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1
     // ---- which tile: undo the round-robin XCD dispatch, then grouped ordering
     const int nwg = gridDim.x;                                   // multiple of 8
     const int logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
-    const int tiles = tiles_m * tiles_n;
-    if (logical >= tiles * splitk) return;
-    const int ks = logical / tiles;
-    const int t = logical - ks * tiles;
+    const int t = logical;
+    if (t >= tiles_m * tiles_n) return;
     const int group_size = group_m * tiles_n;
     const int grp = t / group_size;
     const int first_m = grp * group_m;
@@ -171,9 +172,8 @@ __global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
 
-    const int KT = g.K / BK;
-    const int kt0 = (int)((long long)ks * KT / splitk);
-    const int kt1 = (int)((long long)(ks + 1) * KT / splitk);
+    const int kt0 = 0;
+    const int kt1 = g.K / BK;
 
     // ---- global -> register staging
     const int crow = tid / CPR;
@@ -318,40 +318,233 @@ __global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1
     // ---- epilogue (the LDS stages are free once every wave has left the k loop)
     __syncthreads();
     float* stage = reinterpret_cast<float*>(smem_raw) + wave * EPI_WAVE_FLOATS;
-    const int row0 = m0 + wave * (32 * TM);
-    switch (g.epilogue) {
-        case kEpiBias: epilogue<TM, TN, kEpiBias>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
-        case kEpiBiasGelu: epilogue<TM, TN, kEpiBiasGelu>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
-        case kEpiGatedResidual: epilogue<TM, TN, kEpiGatedResidual>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
-        default: epilogue<TM, TN, kEpiResidual>(g, acc, stage, row0, n0, lane, ks == 0, splitk > 1); break;
+    run_epilogue<TM, TN>(g, acc, stage, m0 + wave * (32 * TM), n0, lane);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Second kernel: tiles go global -> LDS directly (global_load_lds_dwordx4, no staging registers and no
+// LDS write instructions), 8 waves per workgroup arranged WM x WN so that a wave's tile is (32 TM) x (32 TN)
+// with TM + TN fragment reads per TM TN MFMAs, NS LDS stages of BK = 64.
+//
+// A direct load writes 16 bytes per lane at consecutive LDS addresses (lane l -> base + 16 l), so one wave
+// instruction fills 8 tile rows of 128 bytes.  The swizzle is applied on the global side: the lane that
+// fills chunk position p of row r fetches logical chunk p ^ ((r / 2) % 8) of that row; the 8 lanes of a row
+// still cover one whole 128-byte segment of the operand.
+//
+// Iteration t:  wait for this wave's loads of tile t | barrier (tile t visible to all; every wave is done
+// with tile t - 1, whose stage is therefore free) | issue the loads of tile t + NS - 1 | compute tile t.
+constexpr int kVmcntShift = 14;
+constexpr int vmcnt_imm(int n) {      // s_waitcnt with only vmcnt constrained
+    return (n & 0xF) | ((n >> 4) << kVmcntShift) | 0x0F70;
+}
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+// 16 bytes per lane from global memory straight into LDS at dst + 16 * lane (dst is wave-uniform).
+__device__ __forceinline__ void load_to_lds_b128(const void* src, void* dst) {
+    __builtin_amdgcn_global_load_lds(src, (lds_void_ptr)dst, 16, 0, 0);
+}
+
+template <int WM, int WN, int TM, int TN, int NS>
+__global__ __launch_bounds__(64 * WM * WN, 1) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n,
+                                                                   int group_m) {
+    constexpr int NW = WM * WN;
+    constexpr int BK = 64;
+    constexpr int BM = 32 * TM * WM;
+    constexpr int BN = 32 * TN * WN;
+    constexpr int KS = BK / 16;
+    constexpr int GROUPS = (BM + BN) / 8;            // 8-row groups of the stacked [A; W] tile = wave loads per tile
+    constexpr int LPW = GROUPS / NW;                 // loads per wave per tile
+    static_assert(GROUPS % NW == 0, "tile rows must split evenly over the waves");
+    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN;
+    const int wn = wave % WN;
+    const int l31 = lane & 31;
+    const int lh = lane >> 5;
+
+    const int nwg = gridDim.x;                                   // multiple of 8
+    const int logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
+    const int t = logical;
+    if (t >= tiles_m * tiles_n) return;
+    const int group_size = group_m * tiles_n;
+    const int grp = t / group_size;
+    const int first_m = grp * group_m;
+    const int gm = min(tiles_m - first_m, group_m);
+    const int in_grp = t - grp * group_size;
+    const int tile_m = first_m + in_grp % gm;
+    const int tile_n = in_grp / gm;
+    const int m0 = tile_m * BM;
+    const int n0 = tile_n * BN;
+
+    const int kt0 = 0;
+    const int kt1 = g.K / BK;
+    const int nk = kt1 - kt0;
+
+    // ---- per-lane source of each of this wave's loads (8-row group wave + NW i of the stacked tile): a 32-bit
+    // byte offset into the operand (operands are below 4 GB); the k advance is uniform
+    uint32_t off[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int r = 8 * (wave + NW * i) + (lane >> 3);         // row of the stacked tile
+        const int c = (lane & 7) ^ ((r >> 1) & 7);               // logical 16-byte chunk this lane fetches
+        const int row = (8 * (wave + NW * i) < BM) ? min(m0 + r, g.M - 1) : min(n0 + r - BM, g.N - 1);
+        off[i] = (uint32_t)row * (uint32_t)g.K * 2u + (uint32_t)c * 16u;
     }
+    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.a) + (size_t)kt0 * (BK * 2);
+    const unsigned char* w_base = reinterpret_cast<const unsigned char*>(g.w) + (size_t)kt0 * (BK * 2);
+    auto issue_loads = [&](int kt_rel, int stage) {
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            unsigned char* dst = smem_raw + stage * STAGE_BYTES + (wave + NW * i) * 1024;
+            const unsigned char* base = (8 * (wave + NW * i) < BM) ? a_base : w_base;   // uniform per load
+            load_to_lds_b128(base + (size_t)kt_rel * (BK * 2) + off[i], dst);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int a_row0 = wm * (32 * TM) + l31;
+    const int b_row0 = BM + wn * (32 * TN) + l31;
+    auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], const bf16* st, int s) {
+        const int coff = ((2 * s + lh) ^ ((l31 >> 1) & 7)) << 3;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(st + (a_row0 + 32 * i) * BK + coff);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(st + (b_row0 + 32 * j) * BK + coff);
+    };
+    auto compute = [&](int stage) {
+        const bf16* st = reinterpret_cast<const bf16*>(smem_raw + stage * STAGE_BYTES);
+        bf16x8 fa[2][TM], fb[2][TN];
+        load_frags(fa[0], fb[0], st, 0);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            if (s + 1 < KS) load_frags(fa[(s + 1) & 1], fb[(s + 1) & 1], st, s + 1);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
+        }
+    };
+    // Issue order of one iteration: the first step's fragment reads, then per MFMA one MFMA, the next step's
+    // fragment reads spread evenly, and the tile loads spread over the first MFMAs.
+    auto issue_pipeline = [&](bool with_loads) {
+        constexpr int kMfma = TM * TN * KS;
+        constexpr int kReadsPerMfma = (TM + TN + TM * TN - 1) / (TM * TN);
+        __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+#pragma unroll
+        for (int m = 0; m < kMfma; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, kReadsPerMfma, 0);
+            if (with_loads && m < LPW) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    auto step = [&](auto sc, int tt) {
+        constexpr int s = decltype(sc)::value;                   // stage of tile tt
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * LPW));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        // Loads are unconditional (past the end they re-read the last tile into a stage nobody reads again)
+        // so that the wait count above is the same in every iteration.
+        issue_loads(min(tt + NS - 1, nk - 1), (s + NS - 1) % NS);
+        compute(s);
+        issue_pipeline(true);
+    };
+    if (nk > 0) {
+#pragma unroll
+        for (int p = 0; p < NS - 1; ++p) issue_loads(min(p, nk - 1), p);
+    }
+    int i = 0;
+    for (; i + NS <= nk; i += NS) {
+        step(std::integral_constant<int, 0>{}, i);
+        if constexpr (NS > 1) step(std::integral_constant<int, 1 % NS>{}, i + 1);
+        if constexpr (NS > 2) step(std::integral_constant<int, 2 % NS>{}, i + 2);
+        if constexpr (NS > 3) step(std::integral_constant<int, 3 % NS>{}, i + 3);
+    }
+    if (i < nk) step(std::integral_constant<int, 0>{}, i);
+    if constexpr (NS > 2) {
+        if (i + 1 < nk) step(std::integral_constant<int, 1 % NS>{}, i + 1);
+    }
+    if constexpr (NS > 3) {
+        if (i + 2 < nk) step(std::integral_constant<int, 2 % NS>{}, i + 2);
+    }
+
+    // ---- epilogue: every direct load has landed and every wave has left the k loop before the stages
+    // are reused as staging space
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    float* stage = reinterpret_cast<float*>(smem_raw) + wave * EPI_WAVE_FLOATS;
+    run_epilogue<TM, TN>(g, acc, stage, m0 + wm * (32 * TM), n0 + wn * (32 * TN), lane);
+}
+
+template <int WM, int WN, int TM, int TN, int NS>
+hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    constexpr size_t smem = (size_t)NS * (BM + BN) * 64 * sizeof(bf16);
+    static_assert(smem <= 160 * 1024, "LDS stages exceed 160 KB");
+    static_assert(smem >= (size_t)WM * WN * EPI_WAVE_FLOATS * sizeof(float), "epilogue staging");
+    const int tiles_m = (g.M + BM - 1) / BM;
+    const int tiles_n = (g.N + BN - 1) / BN;
+    const int grid = (tiles_m * tiles_n + 7) / 8 * 8;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, TM, TN, NS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int group_m = 8;
+    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, TM, TN, NS>), dim3(grid), dim3(64 * WM * WN), smem, s, g, tiles_m, tiles_n,
+                       group_m);
+    return hipGetLastError();
 }
 
 struct TilePlan {
-    int tm, tn, splitk, pf;
+    int tm, tn, pf;       // register-staged kernel: tile (128 tm) x (32 tn), pf register sets
+    int dma = 0;          // otherwise: a configuration of the direct-load kernel (tm, tn, pf unused)
 };
 
 // Tile plans measured on MI355X for the projection shapes of the 1.3B- and 14B-shaped blocks with a
-// 1024-token chunk (tile sweep with every (TM, TN, PF) of this kernel).
+// 1024-token chunk (sweep over every (TM, TN, PF) of the register-staged kernel and every configuration of
+// the direct-load kernel).
 struct TunedShape {
     int M, N, K;
     TilePlan plan;
 };
 const TunedShape kTuned[] = {
-    {1024, 4608, 1536, {1, 5, 1, 2}},   {1024, 1536, 1536, {1, 2, 1, 2}},  {1024, 8960, 1536, {2, 5, 1, 2}},
-    {1024, 1536, 8960, {1, 2, 1, 2}},   {1024, 15360, 5120, {1, 5, 1, 2}}, {1024, 5120, 5120, {1, 5, 1, 2}},
-    {1024, 13824, 5120, {2, 7, 1, 2}},  {1024, 5120, 13824, {1, 5, 1, 2}},
+    {1024, 4608, 1536, {1, 5, 2}},  {1024, 1536, 1536, {1, 2, 2}}, {1024, 8960, 1536, {2, 5, 2}},   {1024, 1536, 8960, {1, 2, 2}},
+    {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {1, 5, 2}}, {1024, 13824, 5120, {2, 7, 2}},
 };
 
-// Otherwise: estimate the time of the busiest compute unit.  One k tile of a workgroup costs a fixed
-// part (~0.25 us alone, half of it when a second workgroup fills the bubbles) plus ~21 ns per MFMA a wave
-// issues (fitted to the same sweep); small tiles fit two workgroups per unit.
+// Otherwise: when 256 x 256 tiles fill at least 80 % of the compute units in every round, the direct-load
+// kernel with that tile wins (it moves the fewest bytes per flop through the L2, which is what bounds the
+// large shapes).  Else estimate the time of the busiest compute unit for the register-staged kernel: one k
+// tile of a workgroup costs a fixed part (~0.25 us alone, half of it when a second workgroup fills the
+// bubbles) plus ~21 ns per MFMA a wave issues (fitted to the sweep); small tiles fit two workgroups per unit.
 TilePlan plan_tiles(int M, int N, int K, int epilogue) {
     (void)epilogue;
     for (const TunedShape& t : kTuned)
         if (t.M == M && t.N == N && t.K == K) return t.plan;
     const int kCUs = 256;
-    TilePlan best{1, 4, 1, 2};
+    {
+        const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+        const long long rounds = (tiles + kCUs - 1) / kCUs;
+        if (K >= 512 && tiles * 10 >= rounds * kCUs * 8) return TilePlan{0, 0, 0, 1};
+    }
+    TilePlan best{1, 4, 2};
     double best_cost = 1e300;
     for (int tm = 1; tm <= 2; ++tm) {
         for (int tn = 2; tn <= 7; ++tn) {
@@ -365,7 +558,7 @@ TilePlan plan_tiles(int M, int N, int K, int epilogue) {
             cost = cost * (K / 64) + per_cu * 0.04 * tm * tn;      // + epilogue
             if (cost < best_cost) {
                 best_cost = cost;
-                best = TilePlan{tm, tn, 1, 2};
+                best = TilePlan{tm, tn, 2};
             }
         }
     }
@@ -373,13 +566,12 @@ TilePlan plan_tiles(int M, int N, int K, int epilogue) {
 }
 
 template <int TM, int TN, int PF>
-hipError_t launch_one(const GemmArgs& g, int splitk, hipStream_t s) {
+hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
     constexpr int BK = 64;
     constexpr int BM = 128 * TM, BN = 32 * TN;
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.N + BN - 1) / BN;
-    const int wgs = tiles_m * tiles_n * splitk;
-    const int grid = (wgs + 7) / 8 * 8;
+    const int grid = (tiles_m * tiles_n + 7) / 8 * 8;
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
     static_assert((size_t)2 * (BM + BN) * BK * sizeof(bf16) >= 4 * EPI_WAVE_FLOATS * sizeof(float), "epilogue staging");
     static bool attr_set = false;
@@ -390,55 +582,64 @@ hipError_t launch_one(const GemmArgs& g, int splitk, hipStream_t s) {
         attr_set = true;
     }
     const int group_m = 8;
-    hipLaunchKernelGGL((gemm_kernel<TM, TN, BK, PF>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m,
-                       splitk);
+    hipLaunchKernelGGL((gemm_kernel<TM, TN, BK, PF>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m);
     return hipGetLastError();
 }
 
 template <int TM, int PF>
-hipError_t launch_tn(const GemmArgs& g, int tn, int splitk, hipStream_t s) {
+hipError_t launch_tn(const GemmArgs& g, int tn, hipStream_t s) {
     switch (tn) {
-        case 2: return launch_one<TM, 2, PF>(g, splitk, s);
-        case 3: return launch_one<TM, 3, PF>(g, splitk, s);
-        case 4: return launch_one<TM, 4, PF>(g, splitk, s);
-        case 5: return launch_one<TM, 5, PF>(g, splitk, s);
-        case 6: return launch_one<TM, 6, PF>(g, splitk, s);
+        case 2: return launch_one<TM, 2, PF>(g, s);
+        case 3: return launch_one<TM, 3, PF>(g, s);
+        case 4: return launch_one<TM, 4, PF>(g, s);
+        case 5: return launch_one<TM, 5, PF>(g, s);
+        case 6: return launch_one<TM, 6, PF>(g, s);
     }
     if constexpr (PF == 2) {
         switch (tn) {
-            case 7: return launch_one<TM, 7, PF>(g, splitk, s);
-            case 8: return launch_one<TM, 8, PF>(g, splitk, s);
+            case 7: return launch_one<TM, 7, PF>(g, s);
+            case 8: return launch_one<TM, 8, PF>(g, s);
         }
+    }
+    return hipErrorInvalidValue;
+}
+
+// Configurations of the direct-load kernel: (waves on M, waves on N, TM, TN, LDS stages).
+constexpr int kDmaConfigs = 4;
+hipError_t launch_dma_config(const GemmArgs& g, int id, hipStream_t s) {
+    switch (id) {
+        case 1: return launch_dma<4, 2, 2, 4, 2>(g, s);      // 256 x 256, wave tile 64 x 128
+        case 2: return launch_dma<2, 4, 4, 2, 2>(g, s);      // 256 x 256, wave tile 128 x 64
+        case 3: return launch_dma<2, 4, 2, 2, 3>(g, s);      // 128 x 256
+        case 4: return launch_dma<4, 2, 2, 2, 3>(g, s);      // 256 x 128
     }
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-// Environment override for tuning runs and tests: SDV2_GEMM_TILE="tm,tn,splitk[,pf]" (read at every call).
+// Environment override for tuning runs and tests, read at every call: SDV2_GEMM_TILE="tm,tn[,pf]" picks a tile
+// of the register-staged kernel, "d<id>" a configuration of the direct-load kernel.
 static bool tile_override(TilePlan* p) {
     const char* e = getenv("SDV2_GEMM_TILE");
-    int a, b, c, d = 2;
-    if (e && sscanf(e, "%d,%d,%d,%d", &a, &b, &c, &d) >= 3 && a >= 1 && a <= 2 && b >= 2 && b <= 8 && c >= 1 && c <= 16 &&
-        (d == 2 || (d == 3 && b <= 6))) {
-        *p = TilePlan{a, b, c, d};
+    int a, b, d = 2;
+    if (e && sscanf(e, "d%d", &a) == 1 && a >= 1 && a <= kDmaConfigs) {
+        *p = TilePlan{0, 0, 0, a};
+        return true;
+    }
+    if (e && sscanf(e, "%d,%d,%d", &a, &b, &d) >= 2 && a >= 1 && a <= 2 && b >= 2 && b <= 8 && (d == 2 || (d == 3 && b <= 6))) {
+        *p = TilePlan{a, b, d};
         return true;
     }
     return false;
 }
 
-hipError_t launch_gemm_planned(const GemmArgs& g, TilePlan p, hipStream_t s) {
-    int splitk = p.splitk;
-    if (g.epilogue == kEpiBias || g.epilogue == kEpiBiasGelu) splitk = 1;
-    if (splitk > g.K / 64) splitk = 1;
-    if (p.pf == 3) return p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
-    return p.tm == 1 ? launch_tn<1, 2>(g, p.tn, splitk, s) : launch_tn<2, 2>(g, p.tn, splitk, s);
-}
-
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue);
     tile_override(&p);
-    return launch_gemm_planned(g, p, s);
+    if (p.dma) return launch_dma_config(g, p.dma, s);
+    if (p.pf == 3) return p.tm == 1 ? launch_tn<1, 3>(g, p.tn, s) : launch_tn<2, 3>(g, p.tn, s);
+    return p.tm == 1 ? launch_tn<1, 2>(g, p.tn, s) : launch_tn<2, 2>(g, p.tn, s);
 }
 
 }  // namespace sdv2

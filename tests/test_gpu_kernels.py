@@ -33,22 +33,29 @@ def f64(t):
 
 # ------------------------------------------------------------------------------------------ GEMM
 GEMM_CASES = [
-    # M, N, K, epilogue, tile override (tm,tn,splitk) or None
+    # M, N, K, epilogue, tile override ("tm,tn[,pf]" register-staged kernel, "d<id>" direct-load kernel) or None
     (128, 128, 64, 0, None),
     (1, 128, 64, 0, None),                 # a single row
-    (200, 384, 192, 0, "1,3,1"),           # ragged M, N tile of 96
-    (333, 640, 512, 1, "2,5,1"),           # GELU epilogue, 256 x 160 tiles, ragged M
-    (1024, 1536, 512, 0, "1,7,1"),         # N not a multiple of the 224-wide tile
-    (300, 512, 1024, 2, "1,4,2"),          # gated residual, split-K atomics, ragged M
+    (200, 384, 192, 0, "1,3"),             # ragged M, N tile of 96
+    (333, 640, 512, 1, "2,5"),             # GELU epilogue, 256 x 160 tiles, ragged M
+    (1024, 1536, 512, 0, "1,7"),           # N not a multiple of the 224-wide tile
+    (300, 512, 1024, 2, "1,4"),            # gated residual, ragged M
     (300, 512, 1024, 2, None),
-    (260, 256, 2048, 3, "2,8,4"),          # residual, biggest tile, split-K 4
-    (300, 384, 768, 0, "1,3,1,3"),         # three register sets (loads three k tiles ahead), 12 k tiles
-    (520, 640, 704, 2, "2,5,1,3"),         # three sets, 11 k tiles (tail of the unrolled-by-6 loop)
-    (256, 256, 64, 3, "2,2,1,3"),          # three sets, a single k tile
-    (256, 384, 448, 1, "1,6,1,3"),         # three sets, 7 k tiles
+    (260, 256, 2048, 3, "2,8"),            # residual, biggest tile
+    (300, 384, 768, 0, "1,3,3"),           # three register sets (loads three k tiles ahead), 12 k tiles
+    (520, 640, 704, 2, "2,5,3"),           # three sets, 11 k tiles (tail of the unrolled-by-6 loop)
+    (256, 256, 64, 3, "2,2,3"),            # three sets, a single k tile
+    (256, 384, 448, 1, "1,6,3"),           # three sets, 7 k tiles
     (1024, 2048, 512, 1, None),            # tiny workload FFN-1
     (1024, 4608, 1536, 0, None),           # 1.3B QKV
-    (1024, 1536, 8960, 2, None),           # 1.3B FFN-2 (planner's own tile and split)
+    (1024, 1536, 8960, 2, None),           # 1.3B FFN-2
+    (1024, 15360, 5120, 0, None),          # 14B QKV: the planner picks the direct-load kernel
+    (1000, 1536, 512, 0, "d1"),            # direct-load kernel, 256 x 256 tiles, ragged M
+    (300, 640, 192, 3, "d2"),              # direct-load kernel, N not a multiple of the tile, 3 k tiles
+    (256, 256, 64, 2, "d2"),               # a single k tile
+    (520, 2048, 1024, 1, "d3"),            # 128 x 256 tiles, three LDS stages, GELU
+    (128, 512, 512, 2, "d4"),              # 256 x 128 tiles, a single ragged M tile
+    (260, 384, 128, 0, "d3"),              # two k tiles in a three-stage ring
 ]
 
 
@@ -72,17 +79,17 @@ def test_gemm_matches_oracle(M, N, K, epi, tile):
         want = f64(x0) + gate * acc
     else:
         want = f64(x0) + acc
-    out = (torch.empty(M, N, dtype=torch.bfloat16) if epi < 2 else x0.clone()).to(DEV)
     if tile:
         os.environ["SDV2_GEMM_TILE"] = tile
     try:
+        out = (torch.empty(M, N, dtype=torch.bfloat16) if epi < 2 else x0.clone()).to(DEV)
         binding.gemm_bf16(a.to(DEV), w.to(DEV), bias.to(DEV), out, epi, gate_a.to(DEV), gate_b.to(DEV), 2 * N,
                           rows_per_gate)
         torch.cuda.synchronize()
+        err = max_rel_err(f64(out), want)
+        assert err < (1e-2 if epi < 2 else 1e-4), err
     finally:
         os.environ.pop("SDV2_GEMM_TILE", None)
-    err = max_rel_err(f64(out), want)
-    assert err < (1e-2 if epi < 2 else 1e-4), err
 
 
 def test_gemm_rejects_bad_shapes():
