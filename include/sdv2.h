@@ -151,7 +151,10 @@ int32_t sdv2_version(void);
  *
  * Device layout per (layer, stream), cap = S + W rounded up to a multiple of 64:
  *     K    bf16 [n_heads][cap][128]      (post-RMSNorm, post-RoPE keys)
- *     V^T  bf16 [n_heads][128][cap]      (values, slot index contiguous)
+ *     V^T  bf16 [n_heads][128][cap]      (values transposed; slot s sits in column
+ *                                         (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1): inside every group of 16
+ *                                         slots the two middle groups of four trade places, which is the key
+ *                                         order of the attention kernel's accumulators)
  *     ids  int64 [cap]                   (token id held by each slot, written by the append kernel;
  *                                         meaningful only for slots < min(total, S + W))
  * ------------------------------------------------------------------------------------------------ */
@@ -265,7 +268,7 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
  *   K multiple of 64, N multiple of 128 (else SDV2_INVALID_ARG).
  *
  * sdv2_attention_bf16: o[b] = softmax(q[b] K[b]^T / sqrt(128)) V[b] over kv_len[b] slots.
- *   q: bf16 [B, L, C]; k[b]: bf16 [H][cap][128]; vt[b]: bf16 [H][128][cap] (cap multiple of 64,
+ *   q: bf16 [B, L, C]; k[b]: bf16 [H][cap][128]; vt[b]: bf16 [H][128][cap] in the cache's column order (cap multiple of 64,
  *   >= kv_len[b] > 0); o: bf16 [B, L, C].  workspace: sdv2_attention_workspace_bytes(B, L, C, max kv_len).
  * ------------------------------------------------------------------------------------------------ */
 int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_dev, void* out_dev,

@@ -240,6 +240,12 @@ def kv_cache_slot_map(handle, layer, stream_id, n_slots):
     return list(buf)
 
 
+def vt_columns(n):
+    """Column of the V^T cache rows that holds each of the slots 0 .. n-1 (the layout stated in sdv2.h)."""
+    s = torch.arange(n)
+    return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1)
+
+
 def kv_cache_device_ptrs(handle, layer, stream_id):
     k, vt, ids, cap = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_int32()
     _check(_lib.sdv2_kv_cache_device_ptrs(handle, layer, stream_id, C.byref(k), C.byref(vt), C.byref(ids),

@@ -8,18 +8,24 @@
 // needs no [sink | window] segment logic.  The same kernel serves the text cross-attention.
 //
 // Design
-//   * Workgroup = 4 waves = 128 queries of one (stream, head); each wave owns 32 queries.
+//   * Workgroup = 4 waves = 128 queries of one (stream, head); each wave owns 32 queries; two workgroups
+//     per compute unit.
 //   * Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: keys are the rows,
 //     queries the columns, so a lane (column = lane % 32) owns one query: its row maximum and row sum
 //     live in that lane and its partner lane + 32, and the accumulator of S^T is already in the
 //     register layout that the B operand of the second product O^T = V^T P^T wants.  No LDS round
 //     trip for P.
 //   * That needs V^T tiles with keys contiguous, which is why the cache stores values transposed
-//     ([head][128][cap]); K tiles are contiguous 16 KB blocks of the [head][cap][128] key cache.
-//   * K and V^T tiles of 64 keys go global -> registers -> LDS, double buffered.  Rows are swizzled for
-//     the 64-bank LDS: K rows (256 B) XOR the 16-byte chunk index with row % 16; V^T rows (128 B) XOR it
-//     with (row / 2) % 8 and swap the two 8-byte halves of a chunk in rows 16..31 of each block of 32, so
-//     that the 32 lanes of an 8-byte fragment read hit 32 different bank groups.
+//     ([head][128][cap]); inside every group of 16 slots the cache swaps the middle two groups of four
+//     (vt_column), which is the order in which the S^T accumulator holds its keys, so a V^T fragment is one
+//     16-byte LDS read.  K tiles are contiguous 16 KB blocks of the [head][cap][128] key cache.
+//   * K and V^T tiles of 64 keys go global -> LDS directly (global_load_lds_dwordx4), two stages each.  The
+//     LDS swizzle is applied on the global side: K rows (256 B) XOR the 16-byte chunk index with row % 16,
+//     V^T rows (128 B) with (row / 2) % 8, so that fragment reads are conflict free on the 64-bank LDS.
+//   * The loop is software pipelined inside a wave: while the vector unit runs the softmax of tile t, the
+//     matrix unit computes S^T of tile t + 1; the P V product of tile t follows.  The softmax costs about
+//     as many vector cycles as the tile costs matrix cycles, so without this overlap (and that between
+//     the two workgroups of a unit) the matrix unit idles half of the time.
 //   * Skinny launches (few query tiles x heads) split the key range over several workgroups, which
 //     write normalised partial outputs with their (max, sum); a small kernel merges them.
 #include "common.h"
@@ -33,15 +39,22 @@ namespace {
 constexpr int QT = 128;       // queries per workgroup
 constexpr int KT = 64;        // keys per tile
 constexpr int D = kHeadDim;
-constexpr int STAGE = KT * D + D * KT;   // elements per LDS stage: K tile then V^T tile
+constexpr int K_TILE_BYTES = KT * D * 2;
+constexpr int V_TILE_BYTES = D * KT * 2;
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+__device__ __forceinline__ void load_to_lds_b128(const void* src, void* dst) {
+    __builtin_amdgcn_global_load_lds(src, (lds_void_ptr)dst, 16, 0, 0);
+}
 
 __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float scale_log2e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* const sm = reinterpret_cast<bf16*>(smem_raw);
+    unsigned char* const k_stage = smem_raw;                          // [2][64 keys][256 B]
+    unsigned char* const v_stage = smem_raw + 2 * K_TILE_BYTES;       // [2][128 d][128 B]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31;
     const int lh = lane >> 5;
 
@@ -56,6 +69,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
     const int n_tiles = (kv_len + KT - 1) / KT;
     const int t0 = (int)((long long)split * n_tiles / a.splits);
     const int t1 = (int)((long long)(split + 1) * n_tiles / a.splits);
+    const int tail_tile = (kv_len % KT) ? n_tiles - 1 : -1;           // the tile with slots past kv_len, if any
 
     // ---- this lane's query (column of S^T) and its eight d-step fragments
     const int q_in_chunk = qt * QT + wave * 32 + l31;
@@ -67,43 +81,41 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         for (int s = 0; s < D / 16; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
     }
 
-    // ---- global -> register staging of one K tile and one V^T tile
-    const bf16* kbase = a.k[b] + (size_t)h * cap * D;
-    const bf16* vbase = a.vt[b] + (size_t)h * D * cap;
-    bf16x8 rk[4], rv[4];
-    auto gload = [&](int t) {
-        const bf16* kp = kbase + (size_t)t * KT * D;
+    // ---- direct loads.  A wave load fills 1 KB of LDS in lane order: 4 K rows or 8 V^T rows.  Wave w issues
+    // loads w, w + 4, w + 8, w + 12 of each tile; the XOR term of a lane's chunk is the same for all four.
+    const unsigned char* kbase = reinterpret_cast<const unsigned char*>(a.k[b] + (size_t)h * cap * D);
+    const unsigned char* vbase = reinterpret_cast<const unsigned char*>(a.vt[b] + (size_t)h * D * cap);
+    const int k_row = 4 * wave + (lane >> 4);                                     // + 16 i
+    const uint32_t k_off = (uint32_t)k_row * 256u + (uint32_t)(((lane & 15) ^ (k_row & 15)) * 16);
+    const int v_row = 8 * wave + (lane >> 3);                                     // + 32 i
+    const size_t v_off = (size_t)v_row * cap * 2 + (size_t)(((lane & 7) ^ ((v_row >> 1) & 7)) * 16);
+    auto load_k = [&](int t, int stage) {
+        const unsigned char* src = kbase + (size_t)t * K_TILE_BYTES + k_off;
+        unsigned char* dst = k_stage + stage * K_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rk[i] = *reinterpret_cast<const bf16x8*>(kp + (tid + 256 * i) * 8);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx >> 3, c = idx & 7;
-            rv[i] = *reinterpret_cast<const bf16x8*>(vbase + (size_t)row * cap + t * KT + c * 8);
-            const int key0 = t * KT + c * 8;
-            if (key0 + 8 > kv_len) {      // only in the last tile: slots past kv_len may hold anything
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (key0 + e >= kv_len) rv[i][e] = (bf16)0.0f;
-            }
-        }
+        for (int i = 0; i < 4; ++i) load_to_lds_b128(src + i * 4096, dst + i * 4096);
     };
-    auto sstore = [&](int buf) {
-        bf16* sk = sm + buf * STAGE;
-        bf16* sv = sk + KT * D;
+    auto load_v = [&](int t, int stage) {
+        const unsigned char* src = vbase + (size_t)t * (KT * 2) + v_off;
+        unsigned char* dst = v_stage + stage * V_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx >> 4, c = idx & 15;
-            *reinterpret_cast<bf16x8*>(sk + row * D + ((c ^ (row & 15)) << 3)) = rk[i];
-        }
+        for (int i = 0; i < 4; ++i) load_to_lds_b128(src + (size_t)i * 32 * cap * 2, dst + i * 4096);
+    };
+    // Slots past kv_len may hold anything (NaN included) and 0 x NaN is not 0: blank them in the staged V^T tile.
+    auto blank_v_tail = [&](int t, int stage) {
+        const int n_valid = kv_len - t * KT;
+        bf16* sv = reinterpret_cast<bf16*>(v_stage + stage * V_TILE_BYTES);
+        for (int idx = tid; idx < D * 8; idx += 256) {
+            const int row = idx >> 3, p = idx & 7;
+            const int c = p ^ ((row >> 1) & 7);
+            bf16x8 v = *reinterpret_cast<bf16x8*>(sv + row * KT + p * 8);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx >> 3, c = idx & 7;
-            bf16x8 w = rv[i];
-            if (row & 16) w = __builtin_shufflevector(w, w, 4, 5, 6, 7, 0, 1, 2, 3);
-            *reinterpret_cast<bf16x8*>(sv + row * KT + ((c ^ ((row >> 1) & 7)) << 3)) = w;
+            for (int e = 0; e < 8; ++e) {
+                const int u = 8 * c + e;                                          // stored column
+                const int slot = (u & ~12) | ((u & 4) << 1) | ((u & 8) >> 1);     // slot it holds (vt_column is an involution)
+                if (slot >= n_valid) v[e] = (bf16)0.0f;
+            }
+            *reinterpret_cast<bf16x8*>(sv + row * KT + p * 8) = v;
         }
     };
 
@@ -115,58 +127,63 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
     float m_run = -INFINITY;     // running maximum of the scaled (log2-domain) scores of this query
     float l_run = 0.0f;          // this lane's share of the running sum
 
-    // Loads and LDS writes of the next tile are unconditional (the tile index is clamped; the last
-    // iteration re-stages its own tile into the idle buffer) so that the loop body is straight-line code
-    // whose issue order can be laid out explicitly: global loads between the QK^T MFMAs, LDS writes
-    // between the PV MFMAs, fragment reads one step ahead of the MFMAs that use them.
-    if (t0 < t1) {
-        gload(t0);
-        sstore(0);
-    }
-    __syncthreads();
-    for (int t = t0; t < t1; ++t) {
-        const int buf = (t - t0) & 1;
-        const bf16* sk = sm + buf * STAGE;
-        const bf16* sv = sk + KT * D;
-        __builtin_amdgcn_sched_barrier(0);
-        gload(min(t + 1, t1 - 1));
-
-        // ---- S^T = K Q^T for the tile's two blocks of 32 keys
-        f32x16 s_acc[2];
+    // S^T block kb of the tile in stage: eight 16-wide d steps
+    auto qk_block = [&](f32x16& s, const unsigned char* sk, int kb) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+        const unsigned char* row = sk + (kb * 32 + l31) * 256;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s_acc[kb][r] = 0.0f;
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + l31) * D +
-                                                                    (((2 * s + lh) ^ (l31 & 15)) << 3));
-                s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s_acc[kb], 0, 0, 0);
-            }
+        for (int st = 0; st < D / 16; ++st) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(row + (((2 * st + lh) ^ (l31 & 15)) << 4));
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s, 0, 0, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-#pragma unroll
-        for (int m = 0; m < 16; ++m) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (m & 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    };
 
-        // ---- online softmax in the log2 domain: p = 2^(s c - m), m = running maximum of s c
-        const bool tail = (t + 1) * KT > kv_len;
-        if (tail) {
+    auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };       // vmcnt(0) only
+    auto barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    f32x16 s_a[2], s_b[2];
+    // one tile: s_cur holds S^T of tile t; S^T of tile t + 1 is formed into s_nxt on the way
+    auto tile_step = [&](f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], int t) {
+        const int rel = t - t0;
+        wait_loads();
+        barrier();                       // K(t+1) and V(t) have landed; everyone is done with K(t), V(t-1)
+        if (t == tail_tile) {
+            blank_v_tail(t, rel & 1);
+            __syncthreads();
+        }
+        if (t + 2 < t1) load_k(t + 2, rel & 1);
+        if (t + 1 < t1) load_v(t + 1, (rel + 1) & 1);
+        const unsigned char* sk = k_stage + ((rel + 1) & 1) * K_TILE_BYTES;
+        const unsigned char* sv = v_stage + (rel & 1) * V_TILE_BYTES;
+
+        if (t == tail_tile) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= kv_len) s_acc[kb][r] = -INFINITY;
+                    if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= kv_len) s_cur[kb][r] = -INFINITY;
         }
-        float mx = fmaxf(s_acc[0][0], s_acc[1][0]);
+        // ---- first half of S^T(t+1) on the matrix unit | row maximum of tile t on the vector unit.  (Past the
+        // last tile this reads a stale stage and the result is dropped: no branch, so that matrix and vector
+        // instructions share a basic block and can be interleaved.)
+        __builtin_amdgcn_sched_barrier(0);
+        qk_block(s_nxt[0], sk, 0);
+        float mx = fmaxf(s_cur[0][0], s_cur[1][0]);
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s_acc[0][r], s_acc[1][r]));
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s_cur[0][r], s_cur[1][r]));
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         const float m_new = fmaxf(m_run, mx * scale_log2e);     // finite: every tile has a valid key
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        }
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // rescale only when some row's maximum moved
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             l_run *= alpha;
@@ -176,44 +193,65 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
                 for (int r = 0; r < 16; ++r) o_acc[i][r] *= alpha;
             m_run = m_new;
         }
+        // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
+        __builtin_amdgcn_sched_barrier(0);
+        qk_block(s_nxt[1], sk, 1);
         float lsum = 0.0f;
         bf16x8 pf[4];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], scale_log2e, -m_run));
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb][r], scale_log2e, -m_run));
                 lsum += p;
                 pf[kb * 2 + (r >> 3)][r & 7] = (bf16)p;
             }
         }
         l_run += lsum;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {                       // 8 MFMAs, their fragment reads, the vector work between
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 14, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- O^T += V^T P^T : four steps of 16 keys; step ts uses registers 8 (ts % 2) .. +7 of block ts / 2,
-        // i.e. keys 16 ts + 4 (lane / 32) + {0..3} and 16 ts + 8 + 4 (lane / 32) + {0..3}.
+        // ---- O^T += V^T P^T : four steps of 16 keys; step ts uses registers 8 (ts % 2) .. + 7 of block ts / 2,
+        // i.e. slots 16 ts + 4 (lane / 32) + {0..3} and 16 ts + 8 + 4 (lane / 32) + {0..3}: chunk 2 ts + lane / 32
+        // of the V^T row in the cache's column order.
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) {
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                const bf16* vrow = sv + (db * 32 + l31) * KT + 4 * (lh ^ (l31 >> 4));
-                const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ts) ^ ((l31 >> 1) & 7)) << 3));
-                const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vrow + (((2 * ts + 1) ^ ((l31 >> 1) & 7)) << 3));
-                const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+                const unsigned char* vrow = sv + (db * 32 + l31) * 128;
+                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vrow + (((2 * ts + lh) ^ ((l31 >> 1) & 7)) << 4));
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ts], o_acc[db], 0, 0, 0);
             }
         }
-        sstore(buf ^ 1);
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            if (m & 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
+    };
+
+    if (t0 < t1) {
+        load_k(t0, 0);
+        load_v(t0, 0);
+        if (t0 + 1 < t1) load_k(t0 + 1, 1);
+        wait_loads();
+        barrier();
+        qk_block(s_a[0], k_stage, 0);
+        qk_block(s_a[1], k_stage, 1);
     }
+    int t = t0;
+    for (; t + 2 <= t1; t += 2) {
+        tile_step(s_a, s_b, t);
+        tile_step(s_b, s_a, t + 1);
+    }
+    if (t < t1) tile_step(s_a, s_b, t);
 
     // ---- finish: divide by the row sum and write
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
@@ -316,7 +354,7 @@ size_t attention_workspace_bytes(int B, int L, int C, int max_kv_len) {
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
-    const size_t smem = (size_t)2 * STAGE * sizeof(bf16);
+    const size_t smem = (size_t)2 * K_TILE_BYTES + 2 * V_TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel),

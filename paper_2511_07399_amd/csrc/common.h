@@ -17,6 +17,11 @@ constexpr int kWave = 64;
 constexpr int kHeadDim = 128;
 constexpr int kMaxBatch = 8;
 
+// Column of a V^T cache row that holds slot s: inside every group of 16 slots the two middle groups of four
+// trade places (0-3, 8-11, 4-7, 12-15), the order in which the S^T accumulator of the attention kernel holds
+// its keys.  The map is its own inverse.
+__host__ __device__ __forceinline__ int vt_column(int s) { return (s & ~12) | ((s & 4) << 1) | ((s & 8) >> 1); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);

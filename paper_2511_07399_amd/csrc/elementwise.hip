@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void rmsnorm_inplace_kernel(bf16* x, const flo
 // token's ring slot.  The rotation angle is formed in double so that it stays exact for any stream
 // length.
 // Blocks [norm_blocks, ...): one (64-token tile, head) each: v goes through LDS and is written
-// transposed, slot index contiguous, into the V^T cache.
+// transposed into the V^T cache, a slot's column given by vt_column.
 constexpr int VT_TOK = 64;
 constexpr int VT_LD = kHeadDim + 2;     // LDS row stride in elements: odd number of words, no bank conflicts
 
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs a, int 
     const int tok = lane;
     if (tok0 + tok < a.L) {
         const int slot = slot_of(st.g0 + tok0 + tok, a.S, a.W);
-        bf16* vo = st.vt_cache + (size_t)h * kHeadDim * st.cap + slot;
+        bf16* vo = st.vt_cache + (size_t)h * kHeadDim * st.cap + vt_column(slot);
         for (int d = wave * 32; d < wave * 32 + 32; ++d) vo[(size_t)d * st.cap] = tile[tok * VT_LD + d];
     }
 }
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void plain_append_kernel(PlainAppendArgs a, in
     const int tok = lane;
     if (tok0 + tok < a.n) {
         const int slot = slot_of(a.st.g0 + tok0 + tok, a.S, a.W);
-        bf16* vo = a.st.vt_cache + (size_t)h * kHeadDim * a.st.cap + slot;
+        bf16* vo = a.st.vt_cache + (size_t)h * kHeadDim * a.st.cap + vt_column(slot);
         for (int d = wave * 32; d < wave * 32 + 32; ++d) vo[(size_t)d * a.st.cap] = tile[tok * VT_LD + d];
     }
 }

@@ -92,6 +92,7 @@ class DeviceModel:
         ids = self.cache_storage[ip - base:ip - base + cap * 8].view(torch.int64)
         nslot = self.S + self.W
         K = kraw.permute(1, 0, 2).reshape(cap, H * D)[:nslot].float().cpu().numpy()
+        vraw = vraw[:, :, binding.vt_columns(cap).to(vraw.device)]          # column order -> slot order
         V = vraw.permute(2, 0, 1).reshape(cap, H * D)[:nslot].float().cpu().numpy()
         return K, V, ids[:nslot].cpu().numpy()
 

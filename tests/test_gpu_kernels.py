@@ -103,13 +103,14 @@ def test_gemm_rejects_bad_shapes():
 
 # ------------------------------------------------------------------------------------------ attention
 def pack_kv(k_rows, v_rows, H, cap):
-    """Token rows [n, C] -> the cache layouts K [H][cap][128], V^T [H][128][cap]; padding slots are NaN."""
+    """Token rows [n, C] -> the cache layouts K [H][cap][128], V^T [H][128][cap] (slot s in column vt_columns[s]);
+    padding slots are NaN."""
     n, Cw = k_rows.shape
     D = Cw // H
     K = torch.full((H, cap, D), float("nan"), dtype=torch.bfloat16)
     VT = torch.full((H, D, cap), float("nan"), dtype=torch.bfloat16)
     K[:, :n, :] = k_rows.reshape(n, H, D).permute(1, 0, 2)
-    VT[:, :, :n] = v_rows.reshape(n, H, D).permute(1, 2, 0)
+    VT[:, :, binding.vt_columns(cap)[:n]] = v_rows.reshape(n, H, D).permute(1, 2, 0)
     return K.contiguous(), VT.contiguous()
 
 
@@ -193,7 +194,8 @@ def test_append_evict_is_bit_exact(P, Sf, Wf, H, sizes):
         base = storage.data_ptr()
         nb = H * cap * D * 2
         K = storage[kp - base:kp - base + nb].view(torch.bfloat16).view(H, cap, D).permute(1, 0, 2).reshape(cap, Cw)
-        V = storage[vp - base:vp - base + nb].view(torch.bfloat16).view(H, D, cap).permute(2, 0, 1).reshape(cap, Cw)
+        V = storage[vp - base:vp - base + nb].view(torch.bfloat16).view(H, D, cap)
+        V = V[:, :, binding.vt_columns(cap).to(DEV)].permute(2, 0, 1).reshape(cap, Cw)       # column order -> slot order
         ids = storage[ip - base:ip - base + cap * 8].view(torch.int64).cpu().numpy()
         live = want_map >= 0
         assert np.array_equal(ids[:S + W][live], want_map[live])
