@@ -32,6 +32,8 @@
 
 #include <stdlib.h>
 
+#include <type_traits>
+
 namespace sdv2 {
 
 namespace {
@@ -41,6 +43,14 @@ constexpr int KT = 64;        // keys per tile
 constexpr int D = kHeadDim;
 constexpr int K_TILE_BYTES = KT * D * 2;
 constexpr int V_TILE_BYTES = D * KT * 2;
+
+// max of three with one instruction and no NaN canonicalisation of the operands (scores are never NaN for
+// valid slots; masked ones are -inf)
+__device__ __forceinline__ float max3_f32(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 __device__ __forceinline__ void load_to_lds_b128(const void* src, void* dst) {
@@ -127,16 +137,28 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
     float m_run = -INFINITY;     // running maximum of the scaled (log2-domain) scores of this query
     float l_run = 0.0f;          // this lane's share of the running sum
 
-    // S^T block kb of the tile in stage: eight 16-wide d steps
-    auto qk_block = [&](f32x16& s, const unsigned char* sk, int kb) {
+    // Half of S^T of the tile in stage sk: d steps 4 half .. 4 half + 3 of both 32-key blocks.  The eight K
+    // fragments are read first, the MFMAs alternate between the two accumulators (a dependent MFMA would
+    // wait 12 clocks longer for its predecessor).
+    auto qk_half = [&](f32x16 (&s)[2], const unsigned char* sk, int half) {
+        if (half == 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
-        const unsigned char* row = sk + (kb * 32 + l31) * 256;
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int st = 0; st < D / 16; ++st) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(row + (((2 * st + lh) ^ (l31 & 15)) << 4));
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s, 0, 0, 0);
+                for (int r = 0; r < 16; ++r) s[kb][r] = 0.0f;
         }
+        bf16x8 kf[4][2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+                kf[i][kb] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + l31) * 256 +
+                                                             (((2 * (4 * half + i) + lh) ^ (l31 & 15)) << 4));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i][kb], qf[4 * half + i], s[kb], 0, 0, 0);
     };
 
     auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };       // vmcnt(0) only
@@ -148,11 +170,13 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
 
     f32x16 s_a[2], s_b[2];
     // one tile: s_cur holds S^T of tile t; S^T of tile t + 1 is formed into s_nxt on the way
-    auto tile_step = [&](f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], int t) {
+    // (tail: compile-time flag of the one tile that has slots past kv_len, so that the others carry no masking code)
+    auto tile_step = [&](auto tail_c, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], int t) {
+        constexpr bool tail = decltype(tail_c)::value;
         const int rel = t - t0;
         wait_loads();
         barrier();                       // K(t+1) and V(t) have landed; everyone is done with K(t), V(t-1)
-        if (t == tail_tile) {
+        if (tail) {
             blank_v_tail(t, rel & 1);
             __syncthreads();
         }
@@ -161,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         const unsigned char* sk = k_stage + ((rel + 1) & 1) * K_TILE_BYTES;
         const unsigned char* sv = v_stage + (rel & 1) * V_TILE_BYTES;
 
-        if (t == tail_tile) {
+        if (tail) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -172,17 +196,21 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         // last tile this reads a stale stage and the result is dropped: no branch, so that matrix and vector
         // instructions share a basic block and can be interleaved.)
         __builtin_amdgcn_sched_barrier(0);
-        qk_block(s_nxt[0], sk, 0);
-        float mx = fmaxf(s_cur[0][0], s_cur[1][0]);
+        qk_half(s_nxt, sk, 0);
+        float mx = max3_f32(s_cur[0][0], s_cur[1][0], s_cur[0][1]);
+        mx = max3_f32(mx, s_cur[1][1], s_cur[0][2]);
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s_cur[0][r], s_cur[1][r]));
+        for (int r = 2; r < 16; r += 1) {
+            if (r == 2) mx = fmaxf(mx, s_cur[1][2]);
+            else mx = max3_f32(mx, s_cur[0][r], s_cur[1][r]);
+        }
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         const float m_new = fmaxf(m_run, mx * scale_log2e);     // finite: every tile has a valid key
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);       // the eight fragment reads, then MFMA | vector work
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
         }
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // rescale only when some row's maximum moved
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -195,7 +223,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         }
         // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
         __builtin_amdgcn_sched_barrier(0);
-        qk_block(s_nxt[1], sk, 1);
+        qk_half(s_nxt, sk, 1);
         float lsum = 0.0f;
         bf16x8 pf[4];
 #pragma unroll
@@ -208,11 +236,12 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
             }
         }
         l_run += lsum;
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {                       // 8 MFMAs, their fragment reads, the vector work between
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int m = 0; m < 8; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 14, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
 
@@ -228,7 +257,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ts], o_acc[db], 0, 0, 0);
             }
         }
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);       // fragment reads run six ahead of the MFMAs
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -243,15 +272,25 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         if (t0 + 1 < t1) load_k(t0 + 1, 1);
         wait_loads();
         barrier();
-        qk_block(s_a[0], k_stage, 0);
-        qk_block(s_a[1], k_stage, 1);
+        qk_half(s_a, k_stage, 0);
+        qk_half(s_a, k_stage, 1);
     }
+    // full tiles in pairs (the two S^T register sets trade places), then what is left: at most one full tile
+    // and the tail tile
+    const int t_full = (t1 - 1 == tail_tile) ? t1 - 1 : t1;          // tiles [t0, t_full) have 64 valid slots
+    const std::false_type no_tail;
+    const std::true_type with_tail;
     int t = t0;
-    for (; t + 2 <= t1; t += 2) {
-        tile_step(s_a, s_b, t);
-        tile_step(s_b, s_a, t + 1);
+    for (; t + 2 <= t_full; t += 2) {
+        tile_step(no_tail, s_a, s_b, t);
+        tile_step(no_tail, s_b, s_a, t + 1);
     }
-    if (t < t1) tile_step(s_a, s_b, t);
+    if (t < t_full) {
+        tile_step(no_tail, s_a, s_b, t);
+        if (t_full < t1) tile_step(with_tail, s_b, s_a, t_full);
+    } else if (t_full < t1) {
+        tile_step(with_tail, s_a, s_b, t_full);
+    }
 
     // ---- finish: divide by the row sum and write
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
