@@ -6,7 +6,10 @@ chunk of synthetic input, with all inputs, weights and caches already resident i
 workload is the 1.3B-shaped model (30 blocks) at steady state (sink full, window full, so every
 step evicts), one denoising step per chunk.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--no-also]
+
+Besides the headline workload the line carries, under "also", the per-chunk latency of the 14B-shaped
+model (40 blocks) measured the same way on a few steps, so that both model sizes are on record.
 
 Timing: W warm-up steps, then K steps between two torch.cuda.synchronize() calls and a pair of
 events on the stream the library launches on (value = the slower of wall clock and events is not
@@ -32,6 +35,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--workload", default="wan1.3b-step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true", help="skip the secondary 14B-shaped measurement")
     ap.add_argument("--cpu-layers", type=int, default=0, help="blocks the oracle times (0: all, bounded to ~30 s)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run a plain device copy of this many MiB (read + write) three times before the timed "
@@ -54,6 +58,55 @@ def main():
     binding.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = wk.WORKLOADS[args.workload]
+    m = measure(args.workload, args.steps, args.warmup, args.copy_calibration)
+    ms_per_step, wall_ms, kernels, roofline = m["ms_per_step"], m["wall_ms"], m["kernels"], m["roofline"]
+    step_flops, gemm_tflops, attn_tflops, l_kv = m["step_flops"], m["gemm_tflops"], m["attn_tflops"], m["l_kv"]
+    B, L, Cw = wl.B, wl.L, wl.C
+    also = None
+    if not args.no_also and args.workload != "wan14b-step":
+        m2 = measure("wan14b-step", 8, 2, 0)
+        w2 = wk.WORKLOADS["wan14b-step"]
+        also = {"wan14b-step": {
+            "workload": "40 blocks, C %d, %d heads x 128, FFN %d, 1 stream x %d query tokens per chunk, L_kv %d, %d text "
+                        "tokens, 1 denoising step per chunk" % (w2.C, w2.H, w2.F, w2.L, m2["l_kv"], w2.L_t),
+            "value": round(m2["ms_per_step"], 4), "unit": "ms", "steps": 8, "warmup": 2,
+            "step_tflops": round(m2["step_flops"] / (m2["ms_per_step"] * 1e-3) / 1e12, 1),
+            "step_frac_mfma_peak": round(m2["step_flops"] / (m2["ms_per_step"] * 1e-3) / cm.MI355X_BF16_FLOPS, 4),
+            "gemm_tflops": round(m2["gemm_tflops"], 1), "attn_tflops": round(m2["attn_tflops"], 1),
+            "kernels": m2["kernels"]}}
+
+    # ---- oracle on the host cores (a reported baseline, not the target)
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = time_oracle(wl, args.cpu_layers)
+
+    out = {
+        "metric": "per-chunk denoise-step latency", "value": round(ms_per_step, 4), "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": "%s: %d blocks, C %d, %d heads x 128, FFN %d, %d stream(s) x %d query tokens per chunk, "
+                        "sink %d + window %d tokens (steady state, L_kv %d), %d text tokens, 1 denoising step per "
+                        "chunk, fp32 residual stream" % (wl.name, wl.N, Cw, wl.H, wl.F, B, L, wl.S, wl.W, l_kv, wl.L_t),
+            "global_batch": B, "seq_len": L,
+        },
+        "wall_ms_per_step": round(wall_ms, 4),
+        "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
+        "step_frac_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / cm.MI355X_BF16_FLOPS, 4),
+        "gemm_tflops": round(gemm_tflops, 1), "attn_tflops": round(attn_tflops, 1),
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "also": also,
+    }
+    print(json.dumps(out))
+
+
+def measure(workload, steps, warmup, copy_calibration):
+    """Steady-state timing of sdv2_denoise_step on one workload: the headline pass and the per-launch pass."""
+    import numpy as np
+    import torch
+    from paper_2511_07399_amd import binding, cost_model as cm, workloads as wk
+    from paper_2511_07399_amd.runner import DeviceModel
+
+    wl = wk.WORKLOADS[workload]
     dev = "cuda:0"
     B, L, Cw = wl.B, wl.L, wl.C
     gpu = DeviceModel(wl, base_seed=0, device=dev, weight_device=dev)
@@ -62,8 +115,8 @@ def main():
     xs = [torch.stack([wk.chunk_input(wl, c, s, device=dev) for s in range(B)]).contiguous() for c in range(n_inputs)]
     stream = torch.cuda.current_stream()
 
-    if args.copy_calibration:
-        src = torch.empty(args.copy_calibration * (1 << 20) // 4, dtype=torch.float32, device=dev).normal_()
+    if copy_calibration:
+        src = torch.empty(copy_calibration * (1 << 20) // 4, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
@@ -80,7 +133,7 @@ def main():
         ts = [wk.timestep(wl, c, 0, s) for s in range(B)]
         return x, descs, ts
 
-    for _ in range(fill_chunks + args.warmup):
+    for _ in range(fill_chunks + warmup):
         x, descs, ts = one_step(chunk)
         gpu.denoise(x, descs, timesteps=ts)
         chunk += 1
@@ -90,7 +143,7 @@ def main():
     l_kv = st["sink_fill"] + st["win_fill"]
 
     # ---- pass 1: the headline number
-    prepared = [one_step(chunk + i) for i in range(args.steps)]
+    prepared = [one_step(chunk + i) for i in range(steps)]
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -99,20 +152,20 @@ def main():
         gpu.denoise(x, descs, timesteps=ts)
     ev1.record(stream)
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = ev0.elapsed_time(ev1) / args.steps
-    chunk += args.steps
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms_per_step = ev0.elapsed_time(ev1) / steps
+    chunk += steps
     assert all(torch.isfinite(x).all().item() for x, _, _ in prepared[-2:])
 
     # ---- pass 2: same steps again with per-launch events
-    n_launch = args.steps * wl.N * len(binding.LAUNCH_TAGS)
-    prepared = [one_step(chunk + i) for i in range(args.steps)]
+    n_launch = steps * wl.N * len(binding.LAUNCH_TAGS)
+    prepared = [one_step(chunk + i) for i in range(steps)]
     torch.cuda.synchronize()
     binding.prof_begin(n_launch)
     for x, descs, ts in prepared:
         gpu.denoise(x, descs, timesteps=ts)
     samples = binding.prof_end(n_launch)
-    chunk += args.steps
+    chunk += steps
     per_tag = {}
     for tag, ms in samples:
         per_tag.setdefault(tag, []).append(ms)
@@ -153,30 +206,12 @@ def main():
         "flops_per_launch": flops[dom], "traffic": load_traffic(wl.name, "FFN-1 gemm"),
     }
     step_flops = wl.N * cm.block_flops(rows, Cw, wl.F, l_kv, wl.L_t)
-
-    # ---- oracle on the host cores (a reported baseline, not the target)
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
-        cpu_baseline = time_oracle(wl, args.cpu_layers)
-
-    out = {
-        "metric": "per-chunk denoise-step latency", "value": round(ms_per_step, 4), "unit": "ms",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {
-            "workload": "%s: %d blocks, C %d, %d heads x 128, FFN %d, %d stream(s) x %d query tokens per chunk, "
-                        "sink %d + window %d tokens (steady state, L_kv %d), %d text tokens, 1 denoising step per "
-                        "chunk, fp32 residual stream" % (wl.name, wl.N, Cw, wl.H, wl.F, B, L, wl.S, wl.W, l_kv, wl.L_t),
-            "global_batch": B, "seq_len": L,
-        },
-        "wall_ms_per_step": round(wall_ms, 4),
-        "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
-        "step_frac_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / cm.MI355X_BF16_FLOPS, 4),
-        "gemm_tflops": round(gemm_tflops, 1), "attn_tflops": round(attn_tflops, 1),
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
-    }
     gpu.close()
-    print(json.dumps(out))
+    del gpu, xs, prepared
+    torch.cuda.empty_cache()
+    return {"ms_per_step": ms_per_step, "wall_ms": wall_ms, "kernels": kernels, "roofline": roofline,
+            "step_flops": step_flops, "gemm_tflops": gemm_tflops, "attn_tflops": attn_tflops, "l_kv": l_kv}
+
 
 
 def load_traffic(workload, launch_site):

@@ -92,6 +92,23 @@ def test_gemm_matches_oracle(M, N, K, epi, tile):
         os.environ.pop("SDV2_GEMM_TILE", None)
 
 
+def test_gemm_full_size_batched_480p_shape_sampled_rows():
+    """FFN-1 of the 14B-shaped block on 4 streams x 4680 tokens (M 18720, N 13824, K 5120: the direct-load kernel,
+    74 x 54 tiles, ragged last M tile): whole output finite, 48 sampled rows against the oracle."""
+    M, N, K = 18720, 13824, 5120
+    g = torch.Generator(device=DEV).manual_seed(7)
+    a = torch.randn(M, K, generator=g, device=DEV).to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g, device=DEV) * 0.02).to(torch.bfloat16)
+    bias = (torch.randn(N, generator=g, device=DEV) * 0.5).to(torch.bfloat16).float()
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    binding.gemm_bf16(a, w, bias, out, 1)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rows = sorted(set(np.random.default_rng(0).integers(0, M, 44).tolist()) | {0, 255, 256, M - 1})
+    want = oracle.gelu_tanh(oracle_linear(f64(a[rows]), f64(w), f64(bias)))
+    assert max_rel_err(f64(out[rows]), want) < 1e-2
+
+
 def test_gemm_rejects_bad_shapes():
     a = torch.zeros(8, 100, dtype=torch.bfloat16, device=DEV)
     w = torch.zeros(128, 100, dtype=torch.bfloat16, device=DEV)
@@ -158,6 +175,31 @@ def test_attention_matches_oracle(B, L, H, kv_lens, splits):
     for b in range(B):
         err = max_rel_err(got[b], want[b])
         assert err < 1e-2, (b, err)
+
+
+def test_attention_full_size_480p_shape_sampled_queries():
+    """Self-attention of the 14B 480p workload at steady state for one stream (4680 queries, 40 heads, 10 920 resident
+    slots = 170 tiles and a tail of 40): whole output finite, 24 sampled queries x all heads against the oracle."""
+    L, H, D, n = 4680, 40, 128, 10920
+    Cw = H * D
+    cap = (n + 63) // 64 * 64
+    g = torch.Generator(device=DEV).manual_seed(11)
+    q = torch.randn(1, L, Cw, generator=g, device=DEV).to(torch.bfloat16)
+    k_rows = torch.randn(n, Cw, generator=g, device=DEV).to(torch.bfloat16)
+    v_rows = torch.randn(n, Cw, generator=g, device=DEV).to(torch.bfloat16)
+    K = torch.full((H, cap, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    VT = torch.full((H, D, cap), float("nan"), dtype=torch.bfloat16, device=DEV)
+    K[:, :n, :] = k_rows.reshape(n, H, D).permute(1, 0, 2)
+    VT[:, :, binding.vt_columns(cap)[:n].to(DEV)] = v_rows.reshape(n, H, D).permute(1, 2, 0)
+    o = torch.full((1, L, Cw), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(binding.attention_workspace_bytes(1, L, Cw, n), 256), dtype=torch.uint8, device=DEV)
+    binding.attention_bf16(q, [K], [VT], [n], [cap], o, H, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all()
+    rows = sorted(set(np.random.default_rng(1).integers(0, L, 20).tolist()) | {0, 127, 128, L - 1})
+    want = oracle.attention_dense(f64(q[0, rows]).reshape(len(rows), H, D), f64(k_rows).reshape(n, H, D),
+                                  f64(v_rows).reshape(n, H, D)).reshape(len(rows), Cw)
+    assert max_rel_err(f64(o[0, rows]), want) < 1e-2
 
 
 # ------------------------------------------------------------------------------------------ standalone cache
