@@ -19,43 +19,61 @@ __device__ __forceinline__ int slot_of(long long g, int S, int W) {
 }
 
 // ------------------------------------------------------------------ LayerNorm (+ modulation or affine)
-// LN_MAXV = float4 values a lane keeps in registers: C <= 256 * LN_MAXV.
+// Two wavefronts per row, two rows per workgroup: a row of the small model is only 6 KB, and with one
+// wavefront per row the kernel is a chain of latencies (load, two shuffle reductions, store) on a quarter of
+// the chip's wave slots.  Mean and variance come from one pass over the registers, as sums of (x - x[0])
+// and (x - x[0])^2 (shifting by the row's first element keeps the fp32 variance exact enough whatever the
+// row's mean); the two waves of a row exchange their partial sums through LDS.
+// LN_MAXV = float4 values a lane keeps in registers: C <= 512 * LN_MAXV.
 template <int LN_MAXV>
 __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
+    __shared__ float part[2][2][2];                       // [row in workgroup][wave of the row][sum, sum of squares]
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= a.rows) return;
+    const int wave = threadIdx.x >> 6;
+    const int rw = wave >> 1;                             // row in the workgroup
+    const int half = wave & 1;
+    const int t = half * 64 + lane;                       // 0 .. 127 within the row
+    const int row_raw = blockIdx.x * 2 + rw;
+    const bool live = row_raw < a.rows;
+    const int row = live ? row_raw : a.rows - 1;          // a spare half workgroup recomputes the last row, stores nothing
     const int nvec = a.C >> 2;
     const f32x4* xp = reinterpret_cast<const f32x4*>(a.x + (size_t)row * a.C);
+    const float pivot = a.x[(size_t)row * a.C];
     f32x4 v[LN_MAXV];
-    float sum = 0.0f;
+    float sum = 0.0f, sq = 0.0f;
 #pragma unroll
     for (int i = 0; i < LN_MAXV; ++i) {
-        const int idx = lane + 64 * i;
+        const int idx = t + 128 * i;
         if (idx < nvec) {
             v[i] = xp[idx];
-            sum += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
-        }
-    }
-    const float mean = wave_sum(sum) / (float)a.C;
-    float sq = 0.0f;
-#pragma unroll
-    for (int i = 0; i < LN_MAXV; ++i) {
-        const int idx = lane + 64 * i;
-        if (idx < nvec) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float d = v[i][e] - mean;
+                const float d = v[i][e] - pivot;
+                sum += d;
                 sq += d * d;
             }
         }
     }
-    const float rstd = rsqrtf(wave_sum(sq) / (float)a.C + a.eps);
+    sum = wave_sum(sum);
+    sq = wave_sum(sq);
+    if (lane == 0) {
+        part[rw][half][0] = sum;
+        part[rw][half][1] = sq;
+    }
+    __syncthreads();
+    sum = part[rw][0][0] + part[rw][1][0];
+    sq = part[rw][0][1] + part[rw][1][1];
+    const float inv_c = 1.0f / (float)a.C;
+    const float dmean = sum * inv_c;                      // mean - pivot
+    const float var = fmaxf(sq * inv_c - dmean * dmean, 0.0f);
+    const float rstd = rsqrtf(var + a.eps);
+    const float mean = pivot + dmean;
+    if (!live) return;
     const int stream = row / a.rows_per_stream;
     bf16* op = a.out + (size_t)row * a.C;
 #pragma unroll
     for (int i = 0; i < LN_MAXV; ++i) {
-        const int idx = lane + 64 * i;
+        const int idx = t + 128 * i;
         if (idx < nvec) {
             const int c = idx * 4;
             f32x4 sc = *reinterpret_cast<const f32x4*>(a.scale_a + c);
@@ -97,13 +115,14 @@ __global__ __launch_bounds__(256) void rmsnorm_inplace_kernel(bf16* x, const flo
 }
 
 // ------------------------------------------------------------------ q/k RMSNorm + RoPE + append, and V^T append
-// Blocks [0, norm_blocks): one wave per token.  Lane j owns rotation pair j of every head: it reads
-// (x[2j], x[2j+1]) of q and k head by head (256 contiguous bytes per wave and head), reduces the sums
-// of squares over the whole row, then normalises, rotates and writes q to its buffer and k to the
-// token's ring slot.  The rotation angle is formed in double so that it stays exact for any stream
-// length.
+// Blocks [0, norm_blocks): one wave per token.  A lane reads 16 bytes (four rotation pairs) of q and of k per
+// step, four heads per wave load, keeps the row in registers, reduces the sums of squares over the whole row,
+// then normalises, rotates and writes q to its buffer and k to the token's ring slot.  Lane j forms the
+// rotation of pair j, in double so that the angle stays exact for any stream length, and the lanes pick
+// up their four by shuffle.
 // Blocks [norm_blocks, ...): one (64-token tile, head) each: v goes through LDS and is written
 // transposed into the V^T cache, a slot's column given by vt_column.
+constexpr int SDV2_MAX_HEADS_ROPE = 64;   // C <= 8192 and 128 channels per head
 constexpr int VT_TOK = 64;
 constexpr int VT_LD = kHeadDim + 2;     // LDS row stride in elements: odd number of words, no bank conflicts
 
@@ -119,40 +138,67 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs a, int 
         const AppendStream& st = a.st[b];
         const bf16* qp = a.qkv + (size_t)row * 3 * C;
         const bf16* kp = qp + C;
+        // a wave load covers four heads: lane l holds pairs 4 (l % 16) .. + 3 of head l / 16 + 4 it
+        constexpr int kMaxIt = (SDV2_MAX_HEADS_ROPE + 3) / 4;
+        const int hl = lane >> 4;
+        const int p0 = 4 * (lane & 15);                      // first of this lane's four rotation pairs
+        bf16x8 qv[kMaxIt], kv[kMaxIt];
         float sq = 0.0f, sk = 0.0f;
-        for (int h = 0; h < a.H; ++h) {
-            const bf16x2 qv = *reinterpret_cast<const bf16x2*>(qp + h * kHeadDim + 2 * lane);
-            const bf16x2 kv = *reinterpret_cast<const bf16x2*>(kp + h * kHeadDim + 2 * lane);
-            sq += (float)qv[0] * (float)qv[0] + (float)qv[1] * (float)qv[1];
-            sk += (float)kv[0] * (float)kv[0] + (float)kv[1] * (float)kv[1];
+#pragma unroll
+        for (int it = 0; it < kMaxIt; ++it) {
+            const int h = hl + 4 * it;
+            if (h < a.H) {
+                qv[it] = *reinterpret_cast<const bf16x8*>(qp + h * kHeadDim + 2 * p0);
+                kv[it] = *reinterpret_cast<const bf16x8*>(kp + h * kHeadDim + 2 * p0);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    sq += (float)qv[it][e] * (float)qv[it][e];
+                    sk += (float)kv[it][e] * (float)kv[it][e];
+                }
+            }
         }
         const float rq = rsqrtf(wave_sum(sq) / (float)C + a.eps);
         const float rk = rsqrtf(wave_sum(sk) / (float)C + a.eps);
-        // position of the token and this lane's rotation
+        // position of the token; lane j forms the rotation of pair j, then every lane fetches its four
         const int frame = st.frame_pos0 + i / a.tokens_per_frame;
         const int inside = i % a.tokens_per_frame;
         const int axis = a.pair_axis[lane];
         const int pos = axis == 0 ? frame : (axis == 1 ? inside / a.grid_w : inside % a.grid_w);
         double sn, cs;
         sincos((double)pos * a.inv_freq[lane], &sn, &cs);
-        const float cf = (float)cs, sf = (float)sn;
+        const float cf_own = (float)cs, sf_own = (float)sn;
+        float cf[4], sf[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            cf[e] = __shfl(cf_own, p0 + e, kWave);
+            sf[e] = __shfl(sf_own, p0 + e, kWave);
+        }
         const long long g = st.g0 + i;
         const int slot = slot_of(g, a.S, a.W);
         if (lane == 0) st.ids[slot] = g;
         bf16* qo = a.q_out + (size_t)row * C;
-        for (int h = 0; h < a.H; ++h) {
-            const int c = h * kHeadDim + 2 * lane;
-            const bf16x2 qv = *reinterpret_cast<const bf16x2*>(qp + c);
-            const bf16x2 kv = *reinterpret_cast<const bf16x2*>(kp + c);
-            const float q0 = (float)qv[0] * rq * a.g_q[c], q1 = (float)qv[1] * rq * a.g_q[c + 1];
-            const float k0 = (float)kv[0] * rk * a.g_k[c], k1 = (float)kv[1] * rk * a.g_k[c + 1];
-            bf16x2 qr, kr;
-            qr[0] = (bf16)(q0 * cf - q1 * sf);
-            qr[1] = (bf16)(q0 * sf + q1 * cf);
-            kr[0] = (bf16)(k0 * cf - k1 * sf);
-            kr[1] = (bf16)(k0 * sf + k1 * cf);
-            *reinterpret_cast<bf16x2*>(qo + c) = qr;
-            *reinterpret_cast<bf16x2*>(st.k_cache + ((size_t)h * st.cap + slot) * kHeadDim + 2 * lane) = kr;
+#pragma unroll
+        for (int it = 0; it < kMaxIt; ++it) {
+            const int h = hl + 4 * it;
+            if (h < a.H) {
+                const int c = h * kHeadDim + 2 * p0;
+                const f32x4 gq0 = *reinterpret_cast<const f32x4*>(a.g_q + c), gq1 = *reinterpret_cast<const f32x4*>(a.g_q + c + 4);
+                const f32x4 gk0 = *reinterpret_cast<const f32x4*>(a.g_k + c), gk1 = *reinterpret_cast<const f32x4*>(a.g_k + c + 4);
+                bf16x8 qr, kr;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float gqa = e < 2 ? gq0[2 * e] : gq1[2 * e - 4], gqb = e < 2 ? gq0[2 * e + 1] : gq1[2 * e - 3];
+                    const float gka = e < 2 ? gk0[2 * e] : gk1[2 * e - 4], gkb = e < 2 ? gk0[2 * e + 1] : gk1[2 * e - 3];
+                    const float q0 = (float)qv[it][2 * e] * rq * gqa, q1 = (float)qv[it][2 * e + 1] * rq * gqb;
+                    const float k0 = (float)kv[it][2 * e] * rk * gka, k1 = (float)kv[it][2 * e + 1] * rk * gkb;
+                    qr[2 * e] = (bf16)(q0 * cf[e] - q1 * sf[e]);
+                    qr[2 * e + 1] = (bf16)(q0 * sf[e] + q1 * cf[e]);
+                    kr[2 * e] = (bf16)(k0 * cf[e] - k1 * sf[e]);
+                    kr[2 * e + 1] = (bf16)(k0 * sf[e] + k1 * cf[e]);
+                }
+                *reinterpret_cast<bf16x8*>(qo + c) = qr;
+                *reinterpret_cast<bf16x8*>(st.k_cache + ((size_t)h * st.cap + slot) * kHeadDim + 2 * p0) = kr;
+            }
         }
         return;
     }
@@ -278,14 +324,14 @@ __global__ __launch_bounds__(256) void gemv_kernel(const float* x, const bf16* w
 }  // namespace
 
 hipError_t launch_layernorm(const LnArgs& a, hipStream_t s) {
-    const dim3 grid((a.rows + 3) / 4), block(256);
-    const int nv = (a.C + 255) / 256;
-    if (nv <= 2) hipLaunchKernelGGL(layernorm_kernel<2>, grid, block, 0, s, a);
+    const dim3 grid((a.rows + 1) / 2), block(256);
+    const int nv = (a.C + 511) / 512;                   // float4 values per lane: 128 lanes per row
+    if (nv <= 1) hipLaunchKernelGGL(layernorm_kernel<1>, grid, block, 0, s, a);
+    else if (nv <= 3) hipLaunchKernelGGL(layernorm_kernel<3>, grid, block, 0, s, a);
+    else if (nv <= 4) hipLaunchKernelGGL(layernorm_kernel<4>, grid, block, 0, s, a);
     else if (nv <= 6) hipLaunchKernelGGL(layernorm_kernel<6>, grid, block, 0, s, a);
-    else if (nv <= 8) hipLaunchKernelGGL(layernorm_kernel<8>, grid, block, 0, s, a);
-    else if (nv <= 12) hipLaunchKernelGGL(layernorm_kernel<12>, grid, block, 0, s, a);
-    else if (nv <= 20) hipLaunchKernelGGL(layernorm_kernel<20>, grid, block, 0, s, a);
-    else if (nv <= 32) hipLaunchKernelGGL(layernorm_kernel<32>, grid, block, 0, s, a);
+    else if (nv <= 10) hipLaunchKernelGGL(layernorm_kernel<10>, grid, block, 0, s, a);
+    else if (nv <= 16) hipLaunchKernelGGL(layernorm_kernel<16>, grid, block, 0, s, a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
