@@ -490,6 +490,171 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_dma_kernel(GemmArgs g, i
     run_epilogue<TM, TN>(g, acc, stage, m0 + wm * (32 * TM), n0 + wn * (32 * TN), lane);
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// Ring variant of the direct-load kernel: k tiles of 32 in a ring of four LDS stages, eight waves, a branch-free
+// loop body in which a wave issues one direct load every fourth MFMA (the compute unit's loads arrive as an
+// even stream three tiles ahead instead of a burst after the barrier that blocks the issuing waves) and reads
+// the next k step's fragments between the MFMAs of the current one.
+template <int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+    static_assert(WM * WN == 8, "eight waves");
+    constexpr int NW = 8, BK = 32, NS = 4;
+    constexpr int BM = 32 * TM * WM;
+    constexpr int BN = 32 * TN * WN;
+    constexpr int LPW = (BM + BN) / 16 / NW;         // a wave load fills 16 rows of 64 bytes
+    static_assert(LPW == 4 && BM % 128 == 0, "256 x 256 tiles");
+    constexpr int LPW_A = BM / 128;
+    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN;
+    const int wn = wave % WN;
+    const int l31 = lane & 31;
+    const int lh = lane >> 5;
+
+    const int nwg = gridDim.x;
+    const int logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
+    const int t = logical;
+    if (t >= tiles_m * tiles_n) return;
+    const int group_size = group_m * tiles_n;
+    const int grp = t / group_size;
+    const int first_m = grp * group_m;
+    const int gm = min(tiles_m - first_m, group_m);
+    const int in_grp = t - grp * group_size;
+    const int tile_m = first_m + in_grp % gm;
+    const int tile_n = in_grp / gm;
+    const int m0 = tile_m * BM;
+    const int n0 = tile_n * BN;
+    const int nk = g.K / BK;
+
+    uint32_t off[LPW];
+    {
+        const int rsub = 16 * wave + (lane >> 2);
+        const int c = (lane & 3) ^ ((rsub >> 2) & 3);            // 128 i does not change (r / 4) % 4
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int r = rsub + 128 * i;
+            const int row = (i < LPW_A) ? min(m0 + r, g.M - 1) : min(n0 + r - BM, g.N - 1);
+            off[i] = (uint32_t)row * (uint32_t)g.K * 2u + (uint32_t)c * 16u;
+        }
+    }
+    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.a);
+    const unsigned char* w_base = reinterpret_cast<const unsigned char*>(g.w);
+    // load i of tile kt (clamped: past the end the last tile is fetched again into a stage nobody reads) into
+    // the stage of iteration index st
+    auto issue_load = [&](auto ic, int kt, int st) {
+        constexpr int i = decltype(ic)::value;
+        unsigned char* dst = smem_raw + (st & (NS - 1)) * STAGE_BYTES + (wave + NW * i) * 1024;
+        load_to_lds_b128((i < LPW_A ? a_base : w_base) + (size_t)kt * (BK * 2) + off[i], dst);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int a_row0 = wm * (32 * TM) + l31;
+    const int b_row0 = BM + wn * (32 * TN) + l31;
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto read_step = [&](auto sc, int kt) {
+        constexpr int s = decltype(sc)::value;
+        const bf16* st = reinterpret_cast<const bf16*>(smem_raw + (kt & (NS - 1)) * STAGE_BYTES);
+        const int coff = ((2 * s + lh) ^ ((l31 >> 2) & 3)) << 3;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[s][i] = *reinterpret_cast<const bf16x8*>(st + (a_row0 + 32 * i) * BK + coff);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[s][j] = *reinterpret_cast<const bf16x8*>(st + (b_row0 + 32 * j) * BK + coff);
+    };
+    auto mfma_step = [&](auto sc) {
+        constexpr int s = decltype(sc)::value;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s][i], fb[s][j], acc[i][j], 0, 0, 0);
+    };
+    // half an iteration: TM TN MFMAs, TM + TN fragment reads among the first of them, two loads at a quarter and
+    // three quarters
+    auto order_half = [&]() {
+        constexpr int kM = TM * TN;
+#pragma unroll
+        for (int m = 0; m < kM; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (m < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (m == kM / 4 || m == 3 * kM / 4) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+    };
+    auto barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    const std::integral_constant<int, 0> c0;
+    const std::integral_constant<int, 1> c1;
+    const std::integral_constant<int, 2> c2;
+    const std::integral_constant<int, 3> c3;
+    for (int p = 0; p < 3; ++p) {
+        const int kt = min(p, nk - 1);
+        issue_load(c0, kt, p);
+        issue_load(c1, kt, p);
+        issue_load(c2, kt, p);
+        issue_load(c3, kt, p);
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPW));      // tiles 0 and 1 have landed
+    barrier();
+    read_step(c0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int lt = min(kt + 3, nk - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_load(c0, lt, kt + 3);
+        issue_load(c1, lt, kt + 3);
+        read_step(c1, kt);
+        mfma_step(c0);
+        order_half();
+        __builtin_amdgcn_sched_barrier(0);
+        issue_load(c2, lt, kt + 3);
+        issue_load(c3, lt, kt + 3);
+        read_step(c0, min(kt + 1, nk - 1));
+        mfma_step(c1);
+        order_half();
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPW));   // all but the newest tile's loads have landed
+        barrier();
+    }
+
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    float* stage = reinterpret_cast<float*>(smem_raw) + wave * EPI_WAVE_FLOATS;
+    run_epilogue<TM, TN>(g, acc, stage, m0 + wm * (32 * TM), n0 + wn * (32 * TN), lane);
+}
+
+template <int WM, int WN, int TM, int TN>
+hipError_t launch_ring(const GemmArgs& g, hipStream_t s) {
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    constexpr size_t smem = (size_t)4 * (BM + BN) * 32 * sizeof(bf16);
+    static_assert(smem <= 160 * 1024 && smem >= (size_t)8 * EPI_WAVE_FLOATS * sizeof(float), "LDS");
+    const int tiles_m = (g.M + BM - 1) / BM;
+    const int tiles_n = (g.N + BN - 1) / BN;
+    const int grid = (tiles_m * tiles_n + 7) / 8 * 8;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<WM, WN, TM, TN>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 8);
+    return hipGetLastError();
+}
+
 template <int WM, int WN, int TM, int TN, int NS>
 hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
@@ -526,12 +691,12 @@ struct TunedShape {
 };
 const TunedShape kTuned[] = {
     {1024, 4608, 1536, {1, 5, 2}},  {1024, 1536, 1536, {1, 2, 2}}, {1024, 8960, 1536, {2, 5, 2}},   {1024, 1536, 8960, {1, 2, 2}},
-    {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {1, 5, 2}}, {1024, 13824, 5120, {2, 7, 2}},
+    {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {1, 5, 2}},
 };
 
 // Otherwise: when 256 x 256 tiles fill at least 80 % of the compute units in every round, the direct-load
 // kernel with that tile wins (it moves the fewest bytes per flop through the L2, which is what bounds the
-// large shapes).  Else estimate the time of the busiest compute unit for the register-staged kernel: one k
+// large shapes), in its ring variant (+2 to +15 % over the two-stage one on the shapes of the 14B block).  Else estimate the time of the busiest compute unit for the register-staged kernel: one k
 // tile of a workgroup costs a fixed part (~0.25 us alone, half of it when a second workgroup fills the
 // bubbles) plus ~21 ns per MFMA a wave issues (fitted to the sweep); small tiles fit two workgroups per unit.
 TilePlan plan_tiles(int M, int N, int K, int epilogue) {
@@ -542,7 +707,7 @@ TilePlan plan_tiles(int M, int N, int K, int epilogue) {
     {
         const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
         const long long rounds = (tiles + kCUs - 1) / kCUs;
-        if (K >= 512 && tiles * 10 >= rounds * kCUs * 8) return TilePlan{0, 0, 0, 1};
+        if (K >= 512 && tiles * 10 >= rounds * kCUs * 8) return TilePlan{0, 0, 0, 6};
     }
     TilePlan best{1, 4, 2};
     double best_cost = 1e300;
@@ -605,13 +770,15 @@ hipError_t launch_tn(const GemmArgs& g, int tn, hipStream_t s) {
 }
 
 // Configurations of the direct-load kernel: (waves on M, waves on N, TM, TN, LDS stages).
-constexpr int kDmaConfigs = 4;
+constexpr int kDmaConfigs = 6;
 hipError_t launch_dma_config(const GemmArgs& g, int id, hipStream_t s) {
     switch (id) {
         case 1: return launch_dma<4, 2, 2, 4, 2>(g, s);      // 256 x 256, wave tile 64 x 128
         case 2: return launch_dma<2, 4, 4, 2, 2>(g, s);      // 256 x 256, wave tile 128 x 64
         case 3: return launch_dma<2, 4, 2, 2, 3>(g, s);      // 128 x 256
         case 4: return launch_dma<4, 2, 2, 2, 3>(g, s);      // 256 x 128
+        case 5: return launch_ring<4, 2, 2, 4>(g, s);        // 256 x 256, ring of four k32 stages
+        case 6: return launch_ring<2, 4, 4, 2>(g, s);
     }
     return hipErrorInvalidValue;
 }

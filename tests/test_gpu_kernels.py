@@ -56,6 +56,10 @@ GEMM_CASES = [
     (520, 2048, 1024, 1, "d3"),            # 128 x 256 tiles, three LDS stages, GELU
     (128, 512, 512, 2, "d4"),              # 256 x 128 tiles, a single ragged M tile
     (260, 384, 128, 0, "d3"),              # two k tiles in a three-stage ring
+    (1000, 1536, 512, 1, "d5"),            # ring of four k32 stages, GELU, ragged M
+    (300, 640, 192, 2, "d6"),              # ring variant, N not a multiple of the tile, 6 k tiles
+    (256, 256, 64, 3, "d6"),               # two k tiles: fewer than the ring holds
+    (130, 256, 32 * 2, 0, "d5"),           # K = 64
 ]
 
 
