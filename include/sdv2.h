@@ -266,15 +266,20 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
  *               gate_b[(row / rows_per_gate) * gate_b_stride + n]
  *            3: out fp32 [M, N] += acc + bias
  *   K multiple of 64, N multiple of 128 (else SDV2_INVALID_ARG).
+ *   workspace_dev (device, 16-byte aligned; may be NULL with workspace_bytes 0): scratch that lets a shape with few
+ *   output tiles and a long k split the k range over several workgroups per tile (a second small kernel adds the parts in
+ *   k order, so the result does not depend on scheduling).  A workspace smaller than
+ *   sdv2_gemm_workspace_bytes(M, N, K, epilogue) is accepted: the launch then does not split.
  *
  * sdv2_attention_bf16: o[b] = softmax(q[b] K[b]^T / sqrt(128)) V[b] over kv_len[b] slots.
  *   q: bf16 [B, L, C]; k[b]: bf16 [H][cap][128]; vt[b]: bf16 [H][128][cap] in the cache's column order (cap multiple of 64,
  *   >= kv_len[b] > 0); o: bf16 [B, L, C].  workspace: sdv2_attention_workspace_bytes(B, L, C, max kv_len).
  * ------------------------------------------------------------------------------------------------ */
+size_t sdv2_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t epilogue);
 int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_dev, void* out_dev,
                        int32_t M, int32_t N, int32_t K, int32_t epilogue,
                        const float* gate_a_dev, const float* gate_b_dev, int32_t gate_b_stride,
-                       int32_t rows_per_gate, void* hip_stream);
+                       int32_t rows_per_gate, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 size_t sdv2_attention_workspace_bytes(int32_t B, int32_t L, int32_t C, int32_t max_kv_len);
 int32_t sdv2_attention_bf16(const void* q_dev, const void* const* k_dev, const void* const* vt_dev,
                             const int32_t* kv_len_host, const int32_t* cap_host, void* o_dev,

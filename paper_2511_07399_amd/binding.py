@@ -65,7 +65,7 @@ EXPORTS = (
     "sdv2_kv_cache_reset", "sdv2_kv_cache_append_evict", "sdv2_kv_cache_state", "sdv2_kv_cache_slot_map",
     "sdv2_kv_cache_device_ptrs", "sdv2_text_kv_bytes", "sdv2_text_kv_workspace_bytes", "sdv2_text_kv_prepare",
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
-    "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_bf16",
+    "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
 )
 
@@ -115,7 +115,9 @@ def load_library():
     lib.sdv2_denoise_workspace_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
     lib.sdv2_denoise_step.argtypes = [C.POINTER(ModelCfg), C.POINTER(ModelWeights), vp, f32p, C.POINTER(C.c_float),
                                       f32p, C.POINTER(vp), C.POINTER(vp), C.POINTER(ChunkDesc), i32, vp, sz, vp]
-    lib.sdv2_gemm_bf16.argtypes = [vp, vp, f32p, vp, i32, i32, i32, i32, f32p, f32p, i32, i32, vp]
+    lib.sdv2_gemm_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.sdv2_gemm_workspace_bytes.restype = sz
+    lib.sdv2_gemm_bf16.argtypes = [vp, vp, f32p, vp, i32, i32, i32, i32, f32p, f32p, i32, i32, vp, sz, vp]
     lib.sdv2_attention_workspace_bytes.restype = sz
     lib.sdv2_attention_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.sdv2_attention_bf16.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(i32), vp, i32,
@@ -322,7 +324,12 @@ ptr_array = _ptr_array
 
 
 # ------------------------------------------------------------------------------------------ dense helpers
-def gemm_bf16(a, w, bias, out, epilogue=0, gate_a=None, gate_b=None, gate_b_stride=0, rows_per_gate=1):
+def gemm_workspace_bytes(M, N, K, epilogue):
+    load_library()
+    return int(_lib.sdv2_gemm_workspace_bytes(M, N, K, epilogue))
+
+
+def gemm_bf16(a, w, bias, out, epilogue=0, gate_a=None, gate_b=None, gate_b_stride=0, rows_per_gate=1, workspace=None):
     load_library()
     _dev(a, torch.bfloat16)
     _dev(w, torch.bfloat16)
@@ -331,7 +338,8 @@ def gemm_bf16(a, w, bias, out, epilogue=0, gate_a=None, gate_b=None, gate_b_stri
     assert w.shape[1] == K and tuple(out.shape) == (M, N)
     _dev(out, torch.bfloat16 if epilogue in (0, 1) else torch.float32)
     _check(_lib.sdv2_gemm_bf16(_ptr(a), _ptr(w), _ptr(bias), _ptr(out), M, N, K, epilogue, _ptr(gate_a), _ptr(gate_b),
-                               gate_b_stride, rows_per_gate, _stream()))
+                               gate_b_stride, rows_per_gate, _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
 
 
 def attention_workspace_bytes(B, L, C_, max_kv_len):

@@ -266,9 +266,15 @@ int32_t sdv2_kv_cache_append_evict(sdv2_kv_cache* cache, int32_t layer, int32_t 
 }
 
 // ------------------------------------------------------------------------------------------ dense helpers
+size_t sdv2_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t epilogue) {
+    if (M <= 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 3) return 0;
+    return align_up(gemm_splitk_floats(M, N, K, epilogue) * sizeof(float), 256);
+}
+
 int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_dev, void* out_dev, int32_t M,
                        int32_t N, int32_t K, int32_t epilogue, const float* gate_a_dev, const float* gate_b_dev,
-                       int32_t gate_b_stride, int32_t rows_per_gate, void* hip_stream) {
+                       int32_t gate_b_stride, int32_t rows_per_gate, void* workspace_dev, size_t workspace_bytes,
+                       void* hip_stream) {
     if (!a_dev || !w_dev || !out_dev) return fail(SDV2_INVALID_ARG, "null operand");
     if (M <= 0 || N <= 0 || K <= 0) return fail(SDV2_INVALID_ARG, "M, N, K must be positive");
     if (K % 64) return fail(SDV2_INVALID_ARG, "K = %d must be a multiple of 64", K);
@@ -289,6 +295,13 @@ int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_d
     g.gate_b = gate_b_dev;
     g.gate_b_stride = gate_b_stride;
     g.rows_per_gate = rows_per_gate > 0 ? rows_per_gate : 1;
+    g.splitk_partials = nullptr;
+    g.splitk_floats = 0;
+    if (workspace_dev && workspace_bytes) {
+        if (reinterpret_cast<uintptr_t>(workspace_dev) % 16) return fail(SDV2_INVALID_ARG, "workspace must be 16-byte aligned");
+        g.splitk_partials = static_cast<float*>(workspace_dev);
+        g.splitk_floats = workspace_bytes / sizeof(float);
+    }
     HIP_TRY(launch_gemm(g, static_cast<hipStream_t>(hip_stream)), "gemm kernel");
     return SDV2_OK;
 }
@@ -444,6 +457,8 @@ struct BlockWorkspace {
     bf16* u;        // [rows, F]
     float* attn;    // split-KV partials
     size_t attn_bytes;
+    float* gemm_partials;   // split-K partial sums
+    size_t gemm_floats;
     size_t total;
 };
 
@@ -466,6 +481,15 @@ BlockWorkspace carve_block(const sdv2_model_cfg* cfg, int B, int L, int max_kv, 
     const size_t a2 = attention_workspace_bytes(B, L, (int)C, cfg->text_len);
     w.attn_bytes = a1 > a2 ? a1 : a2;
     w.attn = reinterpret_cast<float*>(take(w.attn_bytes));
+    // split-K room for the largest need among the block's six projections
+    const int shapes[6][3] = {{(int)(3 * C), (int)C, kEpiBias}, {(int)C, (int)C, kEpiGatedResidual}, {(int)C, (int)C, kEpiBias},
+                              {(int)C, (int)C, kEpiResidual},   {(int)F, (int)C, kEpiBiasGelu},      {(int)C, (int)F, kEpiGatedResidual}};
+    w.gemm_floats = 0;
+    for (const auto& sh : shapes) {
+        const size_t f = gemm_splitk_floats((int)rows, sh[0], sh[1], sh[2]);
+        if (f > w.gemm_floats) w.gemm_floats = f;
+    }
+    w.gemm_partials = reinterpret_cast<float*>(take(w.gemm_floats * sizeof(float)));
     w.total = off;
     return w;
 }
@@ -579,6 +603,8 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     // 2. QKV projection
     GemmArgs g;
     memset(&g, 0, sizeof(g));
+    g.splitk_partials = ws.gemm_floats ? ws.gemm_partials : nullptr;
+    g.splitk_floats = ws.gemm_floats;
     g.M = rows;
     g.rows_per_gate = L;
     g.gate_b_stride = 6 * C;

@@ -37,7 +37,8 @@ __device__ __forceinline__ float gelu_tanh_f(float x) {
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
 // ---------------------------------------------------------------- launchers (host side)
-enum GemmEpilogue { kEpiBias = 0, kEpiBiasGelu = 1, kEpiGatedResidual = 2, kEpiResidual = 3 };
+enum GemmEpilogue { kEpiBias = 0, kEpiBiasGelu = 1, kEpiGatedResidual = 2, kEpiResidual = 3,
+                    kEpiPartial = 4 /* internal: fp32 partial sums of one k part, no bias */ };
 
 struct GemmArgs {
     const bf16* a;        // [M, K]
@@ -50,8 +51,15 @@ struct GemmArgs {
     const float* gate_b;  // [(M / rows_per_gate), gate_b_stride]
     int gate_b_stride;
     int rows_per_gate;
+    // Optional scratch for shapes whose plan splits the k range over several workgroups per tile (null: never
+    // split): room for splitk_floats fp32 partial sums.  A second, elementwise kernel adds the parts in k order
+    // and applies the epilogue, so the result does not depend on scheduling.
+    float* splitk_partials;
+    size_t splitk_floats;
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+// fp32 partial sums the planned launch of an [M, K] x [N, K] product needs (0: its plan does not split k)
+size_t gemm_splitk_floats(int M, int N, int K, int epilogue);
 
 struct AttnArgs {
     const bf16* q;                    // [B, L, C]

@@ -17,9 +17,11 @@
 //   * Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the kernel undoes that
 //     so that each XCD (one L2) owns a contiguous range of tiles, ordered in groups of M tiles that
 //     share weight tiles.
-//   * The k range is never split over workgroups: fp32 atomics on the output cost ~40 us per 1.5 M elements
-//     here, and a last-arriver reduction through memory needs device-scope fences that write back and
-//     invalidate the whole L2 of an XCD (measured +100 us on a 64 us launch).
+//   * Split-K, for the one kind of shape that needs it (few output tiles, long k: FFN-2 of the small model),
+//     is two launches: the parts store fp32 partial sums, an elementwise kernel adds them in k order and applies
+//     the epilogue.  fp32 atomics on the output cost ~40 us per 1.5 M elements here, and a last-arriver
+//     reduction inside one launch needs device-scope fences that write back and invalidate the whole L2 of an
+//     XCD (measured +100 us on a 64 us launch).
 #include "common.h"
 
 #include <type_traits>
@@ -88,7 +90,9 @@ __device__ __forceinline__ void epilogue_chunk(const GemmArgs& g, const f32x16& 
             v += bias;
             if (col_ok && grow < g.M) {
                 const size_t o = (size_t)grow * g.N + gcol;
-                if (EPI == kEpiBias || EPI == kEpiBiasGelu) {
+                if (EPI == kEpiPartial) {
+                    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.out) + o) = v;
+                } else if (EPI == kEpiBias || EPI == kEpiBiasGelu) {
                     bf16x4 w;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) w[e] = (bf16)(EPI == kEpiBiasGelu ? gelu_tanh_f(v[e]) : v[e]);
@@ -126,6 +130,7 @@ __device__ __forceinline__ void run_epilogue(const GemmArgs& g, f32x16 (&acc)[TM
         case kEpiBias: epilogue<TM, TN, kEpiBias>(g, acc, stage, row0, col0, lane); break;
         case kEpiBiasGelu: epilogue<TM, TN, kEpiBiasGelu>(g, acc, stage, row0, col0, lane); break;
         case kEpiGatedResidual: epilogue<TM, TN, kEpiGatedResidual>(g, acc, stage, row0, col0, lane); break;
+        case kEpiPartial: epilogue<TM, TN, kEpiPartial>(g, acc, stage, row0, col0, lane); break;
         default: epilogue<TM, TN, kEpiResidual>(g, acc, stage, row0, col0, lane); break;
     }
 }
@@ -139,7 +144,8 @@ __device__ __forceinline__ void run_epilogue(const GemmArgs& g, f32x16 (&acc)[TM
 // unit get there with three sets, small tiles with two sets and two or three workgroups per unit.
 template <int TM, int TN, int BK, int PF>
 __global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1)) void gemm_kernel(GemmArgs g, int tiles_m,
-                                                                                                  int tiles_n, int group_m) {
+                                                                                                  int tiles_n, int group_m,
+                                                                                                  int splitk) {
     constexpr int BM = 128 * TM;
     constexpr int BN = 32 * TN;
     constexpr int CPR = BK / 8;                 // 16-byte chunks per LDS row
@@ -160,8 +166,10 @@ __global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1
     // ---- which tile: undo the round-robin XCD dispatch, then grouped ordering
     const int nwg = gridDim.x;                                   // multiple of 8
     const int logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
-    const int t = logical;
-    if (t >= tiles_m * tiles_n) return;
+    const int tiles = tiles_m * tiles_n;
+    if (logical >= tiles * splitk) return;
+    const int ks = logical / tiles;                              // which part of k (0 when k is not split)
+    const int t = logical - ks * tiles;
     const int group_size = group_m * tiles_n;
     const int grp = t / group_size;
     const int first_m = grp * group_m;
@@ -172,8 +180,14 @@ __global__ __launch_bounds__(256, ((TM * TN <= 5 && BK == 64 && PF == 2) ? 2 : 1
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
 
-    const int kt0 = 0;
-    const int kt1 = g.K / BK;
+    const int KT = g.K / BK;
+    const int kt0 = (int)((long long)ks * KT / splitk);
+    const int kt1 = (int)((long long)(ks + 1) * KT / splitk);
+    if (splitk > 1) {                                            // this part's fp32 partial sums, plain stores
+        g.out = g.splitk_partials + (size_t)ks * g.M * g.N;
+        g.epilogue = kEpiPartial;
+        g.bias = nullptr;
+    }
 
     // ---- global -> register staging
     const int crow = tid / CPR;
@@ -680,6 +694,7 @@ hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
 struct TilePlan {
     int tm, tn, pf;       // register-staged kernel: tile (128 tm) x (32 tn), pf register sets
     int dma = 0;          // otherwise: a configuration of the direct-load kernel (tm, tn, pf unused)
+    int splitk = 1;       // register-staged kernel: parts of the k range, each its own workgroup (needs scratch)
 };
 
 // Tile plans measured on MI355X for the projection shapes of the 1.3B- and 14B-shaped blocks with a
@@ -690,7 +705,7 @@ struct TunedShape {
     TilePlan plan;
 };
 const TunedShape kTuned[] = {
-    {1024, 4608, 1536, {1, 5, 2}},  {1024, 1536, 1536, {1, 2, 2}}, {1024, 8960, 1536, {2, 5, 2}},   {1024, 1536, 8960, {1, 2, 2}},
+    {1024, 4608, 1536, {1, 5, 2}},  {1024, 1536, 1536, {1, 2, 2}}, {1024, 8960, 1536, {2, 5, 2}},   {1024, 1536, 8960, {1, 4, 2, 0, 5}},
     {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {1, 5, 2}},
 };
 
@@ -731,12 +746,12 @@ TilePlan plan_tiles(int M, int N, int K, int epilogue) {
 }
 
 template <int TM, int TN, int PF>
-hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
+hipError_t launch_one(const GemmArgs& g, int splitk, hipStream_t s) {
     constexpr int BK = 64;
     constexpr int BM = 128 * TM, BN = 32 * TN;
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.N + BN - 1) / BN;
-    const int grid = (tiles_m * tiles_n + 7) / 8 * 8;
+    const int grid = (tiles_m * tiles_n * splitk + 7) / 8 * 8;
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
     static_assert((size_t)2 * (BM + BN) * BK * sizeof(bf16) >= 4 * EPI_WAVE_FLOATS * sizeof(float), "epilogue staging");
     static bool attr_set = false;
@@ -747,23 +762,23 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
         attr_set = true;
     }
     const int group_m = 8;
-    hipLaunchKernelGGL((gemm_kernel<TM, TN, BK, PF>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m);
+    hipLaunchKernelGGL((gemm_kernel<TM, TN, BK, PF>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m, splitk);
     return hipGetLastError();
 }
 
 template <int TM, int PF>
-hipError_t launch_tn(const GemmArgs& g, int tn, hipStream_t s) {
+hipError_t launch_tn(const GemmArgs& g, int tn, int splitk, hipStream_t s) {
     switch (tn) {
-        case 2: return launch_one<TM, 2, PF>(g, s);
-        case 3: return launch_one<TM, 3, PF>(g, s);
-        case 4: return launch_one<TM, 4, PF>(g, s);
-        case 5: return launch_one<TM, 5, PF>(g, s);
-        case 6: return launch_one<TM, 6, PF>(g, s);
+        case 2: return launch_one<TM, 2, PF>(g, splitk, s);
+        case 3: return launch_one<TM, 3, PF>(g, splitk, s);
+        case 4: return launch_one<TM, 4, PF>(g, splitk, s);
+        case 5: return launch_one<TM, 5, PF>(g, splitk, s);
+        case 6: return launch_one<TM, 6, PF>(g, splitk, s);
     }
     if constexpr (PF == 2) {
         switch (tn) {
-            case 7: return launch_one<TM, 7, PF>(g, s);
-            case 8: return launch_one<TM, 8, PF>(g, s);
+            case 7: return launch_one<TM, 7, PF>(g, splitk, s);
+            case 8: return launch_one<TM, 8, PF>(g, splitk, s);
         }
     }
     return hipErrorInvalidValue;
@@ -785,8 +800,8 @@ hipError_t launch_dma_config(const GemmArgs& g, int id, hipStream_t s) {
 
 }  // namespace
 
-// Environment override for tuning runs and tests, read at every call: SDV2_GEMM_TILE="tm,tn[,pf]" picks a tile
-// of the register-staged kernel, "d<id>" a configuration of the direct-load kernel.
+// Environment override for tuning runs and tests, read at every call: SDV2_GEMM_TILE="tm,tn[,pf[,splitk]]" picks a
+// tile of the register-staged kernel, "d<id>" a configuration of the direct-load kernel.
 static bool tile_override(TilePlan* p) {
     const char* e = getenv("SDV2_GEMM_TILE");
     int a, b, d = 2;
@@ -794,19 +809,73 @@ static bool tile_override(TilePlan* p) {
         *p = TilePlan{0, 0, 0, a};
         return true;
     }
-    if (e && sscanf(e, "%d,%d,%d", &a, &b, &d) >= 2 && a >= 1 && a <= 2 && b >= 2 && b <= 8 && (d == 2 || (d == 3 && b <= 6))) {
-        *p = TilePlan{a, b, d};
+    int k = 1;
+    if (e && sscanf(e, "%d,%d,%d,%d", &a, &b, &d, &k) >= 2 && a >= 1 && a <= 2 && b >= 2 && b <= 8 &&
+        (d == 2 || (d == 3 && b <= 6)) && k >= 1 && k <= 8) {
+        *p = TilePlan{a, b, d, 0, k};
         return true;
     }
     return false;
+}
+
+namespace {
+// out = epilogue(sum of the k parts + bias), four columns per thread; the parts are added in k order.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int splitk) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // over M * N / 4
+    const size_t n4 = (size_t)(g.N >> 2);
+    if (idx >= (size_t)g.M * n4) return;
+    const int row = (int)(idx / n4);
+    const int col = (int)(idx - (size_t)row * n4) * 4;
+    const size_t o = (size_t)row * g.N + col;
+    const size_t part = (size_t)g.M * g.N;
+    f32x4 v = *reinterpret_cast<const f32x4*>(g.splitk_partials + o);
+    for (int s = 1; s < splitk; ++s) v += *reinterpret_cast<const f32x4*>(g.splitk_partials + s * part + o);
+    if (g.bias != nullptr) v += *reinterpret_cast<const f32x4*>(g.bias + col);
+    if (g.epilogue == kEpiBias || g.epilogue == kEpiBiasGelu) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16)(g.epilogue == kEpiBiasGelu ? gelu_tanh_f(v[e]) : v[e]);
+        *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(g.out) + o) = w;
+    } else {
+        if (g.epilogue == kEpiGatedResidual) {
+            const f32x4 ga = *reinterpret_cast<const f32x4*>(g.gate_a + col);
+            const f32x4 gb = *reinterpret_cast<const f32x4*>(g.gate_b + (size_t)(row / g.rows_per_gate) * g.gate_b_stride + col);
+            v *= (ga + gb);
+        }
+        float* xo = reinterpret_cast<float*>(g.out) + o;
+        *reinterpret_cast<f32x4*>(xo) = *reinterpret_cast<const f32x4*>(xo) + v;
+    }
+}
+}  // namespace
+
+// Parts of k the plan can really use for this problem and scratch (1: no split).
+static int usable_splitk(const GemmArgs& g, const TilePlan& p) {
+    if (p.dma || p.splitk <= 1 || g.splitk_partials == nullptr) return 1;
+    int splitk = p.splitk;
+    if (splitk > g.K / 128) splitk = g.K / 128;                 // at least two k tiles per part
+    if (splitk < 2 || (size_t)splitk * g.M * g.N > g.splitk_floats) return 1;
+    return splitk;
 }
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue);
     tile_override(&p);
     if (p.dma) return launch_dma_config(g, p.dma, s);
-    if (p.pf == 3) return p.tm == 1 ? launch_tn<1, 3>(g, p.tn, s) : launch_tn<2, 3>(g, p.tn, s);
-    return p.tm == 1 ? launch_tn<1, 2>(g, p.tn, s) : launch_tn<2, 2>(g, p.tn, s);
+    const int splitk = usable_splitk(g, p);
+    hipError_t e;
+    if (p.pf == 3) e = p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
+    else e = p.tm == 1 ? launch_tn<1, 2>(g, p.tn, splitk, s) : launch_tn<2, 2>(g, p.tn, splitk, s);
+    if (e != hipSuccess || splitk == 1) return e;
+    const size_t n = (size_t)g.M * (g.N >> 2);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, g, splitk);
+    return hipGetLastError();
+}
+
+size_t gemm_splitk_floats(int M, int N, int K, int epilogue) {
+    TilePlan p = plan_tiles(M, N, K, epilogue);
+    tile_override(&p);
+    if (p.dma || p.splitk <= 1) return 0;
+    return (size_t)p.splitk * M * N;
 }
 
 }  // namespace sdv2

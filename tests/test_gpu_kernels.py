@@ -33,7 +33,7 @@ def f64(t):
 
 # ------------------------------------------------------------------------------------------ GEMM
 GEMM_CASES = [
-    # M, N, K, epilogue, tile override ("tm,tn[,pf]" register-staged kernel, "d<id>" direct-load kernel) or None
+    # M, N, K, epilogue, tile override ("tm,tn[,pf[,parts of k]]" register-staged kernel, "d<id>" direct-load kernel) or None
     (128, 128, 64, 0, None),
     (1, 128, 64, 0, None),                 # a single row
     (200, 384, 192, 0, "1,3"),             # ragged M, N tile of 96
@@ -60,6 +60,10 @@ GEMM_CASES = [
     (300, 640, 192, 2, "d6"),              # ring variant, N not a multiple of the tile, 6 k tiles
     (256, 256, 64, 3, "d6"),               # two k tiles: fewer than the ring holds
     (130, 256, 32 * 2, 0, "d5"),           # K = 64
+    (300, 512, 1024, 2, "1,4,2,2"),        # k split in two parts + reduce kernel, gated residual, ragged M
+    (260, 256, 2048, 3, "2,8,2,4"),        # four parts, residual
+    (1024, 1536, 1536, 1, "1,5,2,3"),      # three parts, GELU in the reduce kernel, ragged N tile
+    (130, 384, 192, 0, "1,3,2,8"),         # more parts asked than k allows: clamped to one part per two k tiles
 ]
 
 
@@ -86,12 +90,16 @@ def test_gemm_matches_oracle(M, N, K, epi, tile):
     if tile:
         os.environ["SDV2_GEMM_TILE"] = tile
     try:
-        out = (torch.empty(M, N, dtype=torch.bfloat16) if epi < 2 else x0.clone()).to(DEV)
-        binding.gemm_bf16(a.to(DEV), w.to(DEV), bias.to(DEV), out, epi, gate_a.to(DEV), gate_b.to(DEV), 2 * N,
-                          rows_per_gate)
-        torch.cuda.synchronize()
-        err = max_rel_err(f64(out), want)
-        assert err < (1e-2 if epi < 2 else 1e-4), err
+        # with the scratch the plan asks for (NaN-filled: every partial sum that is read was written), then without
+        ws_bytes = binding.gemm_workspace_bytes(M, N, K, epi)
+        ws = torch.full((ws_bytes // 4,), float("nan"), dtype=torch.float32, device=DEV) if ws_bytes else None
+        for workspace in ([ws, None] if ws is not None else [None]):
+            out = (torch.empty(M, N, dtype=torch.bfloat16) if epi < 2 else x0.clone()).to(DEV)
+            binding.gemm_bf16(a.to(DEV), w.to(DEV), bias.to(DEV), out, epi, gate_a.to(DEV), gate_b.to(DEV), 2 * N,
+                              rows_per_gate, workspace=workspace)
+            torch.cuda.synchronize()
+            err = max_rel_err(f64(out), want)
+            assert err < (1e-2 if epi < 2 else 1e-4), err
     finally:
         os.environ.pop("SDV2_GEMM_TILE", None)
 
