@@ -665,7 +665,9 @@ hipError_t launch_ring(const GemmArgs& g, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 8);
+    // groups of four tile rows: an XCD's 32 concurrent tiles then cover 4 x 8 tiles, the shape with the fewest
+    // distinct operand rows per k step
+    hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 4);
     return hipGetLastError();
 }
 
@@ -685,7 +687,7 @@ hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int group_m = 8;
+    const int group_m = (32 * TM * WM >= 256) ? 4 : 8;
     hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, TM, TN, NS>), dim3(grid), dim3(64 * WM * WN), smem, s, g, tiles_m, tiles_n,
                        group_m);
     return hipGetLastError();
