@@ -29,9 +29,13 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 __device__ __forceinline__ float gelu_tanh_f(float x) {
-    // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return x / (1.0f + __expf(-2.0f * u));
+    // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3).  The exponent is formed
+    // directly in base 2 and the quotient is x times the hardware reciprocal (1 ulp): the caller rounds the
+    // result to bf16.
+    constexpr float k1 = -2.0f * 1.4426950408889634f * 0.7978845608028654f;
+    constexpr float k3 = k1 * 0.044715f;
+    const float e = __builtin_amdgcn_exp2f(x * fmaf(x * x, k3, k1));
+    return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
