@@ -68,10 +68,18 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
     const int l31 = lane & 31;
     const int lh = lane >> 5;
 
-    const int qt = blockIdx.x;
-    const int h = blockIdx.y;
-    const int b = blockIdx.z / a.splits;
-    const int split = blockIdx.z - b * a.splits;
+    // Workgroups are handed to the eight XCDs in turn; renumber them so that each XCD (its own L2) works through
+    // a contiguous run of (query tile, head, stream/split) triples, query tile fastest: the workgroups that
+    // share a head's K and V then sit behind the same L2.
+    const unsigned n_wg = gridDim.x * gridDim.y * gridDim.z;
+    const unsigned flat = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned xcd = flat & 7u, per = n_wg >> 3, rem = n_wg & 7u;
+    const unsigned logical = xcd * per + min(xcd, rem) + (flat >> 3);
+    const int qt = (int)(logical % gridDim.x);
+    const int h = (int)((logical / gridDim.x) % gridDim.y);
+    const int bz = (int)(logical / (gridDim.x * gridDim.y));
+    const int b = bz / a.splits;
+    const int split = bz - b * a.splits;
     const int C = a.H * D;
 
     const int kv_len = a.kv_len[b];
