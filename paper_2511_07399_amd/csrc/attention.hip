@@ -52,6 +52,18 @@ __device__ __forceinline__ float max3_f32(float a, float b, float c) {
     return r;
 }
 
+__device__ __forceinline__ float max2_f32(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+// max of x over the lane pair (l, l ^ 32): one swap of the two 32-lane halves on the vector unit (a shuffle
+// through the LDS crossbar would put its latency on the path to the exponentials)
+__device__ __forceinline__ float max_xor32(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return max2_f32(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 __device__ __forceinline__ void load_to_lds_b128(const void* src, void* dst) {
     __builtin_amdgcn_global_load_lds(src, (lds_void_ptr)dst, 16, 0, 0);
@@ -205,14 +217,17 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         // instructions share a basic block and can be interleaved.)
         __builtin_amdgcn_sched_barrier(0);
         qk_half(s_nxt, sk, 0);
-        float mx = max3_f32(s_cur[0][0], s_cur[1][0], s_cur[0][1]);
-        mx = max3_f32(mx, s_cur[1][1], s_cur[0][2]);
+        // four independent chains (a dependent vector instruction waits about twice as long as an independent one)
+        float mc[4];
 #pragma unroll
-        for (int r = 2; r < 16; r += 1) {
-            if (r == 2) mx = fmaxf(mx, s_cur[1][2]);
-            else mx = max3_f32(mx, s_cur[0][r], s_cur[1][r]);
+        for (int c = 0; c < 4; ++c) {
+            mc[c] = max3_f32(s_cur[0][4 * c], s_cur[1][4 * c], s_cur[0][4 * c + 1]);
+            mc[c] = max3_f32(mc[c], s_cur[1][4 * c + 1], s_cur[0][4 * c + 2]);
+            mc[c] = max3_f32(mc[c], s_cur[1][4 * c + 2], s_cur[0][4 * c + 3]);
+            mc[c] = max2_f32(mc[c], s_cur[1][4 * c + 3]);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        float mx = max2_f32(max3_f32(mc[0], mc[1], mc[2]), mc[3]);
+        mx = max_xor32(mx);
         const float m_new = fmaxf(m_run, mx * scale_log2e);     // finite: every tile has a valid key
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);       // the eight fragment reads, then MFMA | vector work
 #pragma unroll
@@ -232,17 +247,18 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
         // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
         __builtin_amdgcn_sched_barrier(0);
         qk_half(s_nxt, sk, 1);
-        float lsum = 0.0f;
+        float ls[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         bf16x8 pf[4];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb][r], scale_log2e, -m_run));
-                lsum += p;
+                ls[r & 3] += p;
                 pf[kb * 2 + (r >> 3)][r & 7] = (bf16)p;
             }
         }
+        const float lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
         l_run += lsum;
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
