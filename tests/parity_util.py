@@ -57,11 +57,12 @@ class OracleRunner:
 
 
 def run_stream_both(wl, n_chunks, steps=1, device="cuda:0", base_seed=0, use_timesteps=None, n_layers=None,
-                    check_cache=True):
+                    check_cache=True, cache_chunks=None):
     """Single stream, ``n_chunks`` chunks of ``steps`` denoising steps, on both sides.
 
     Returns per-chunk output errors, and whether host state, host slot map and device id map equal the
-    oracle's after every chunk; cache contents are compared on resident slots.
+    oracle's after every chunk; cache contents are compared on resident slots (after every chunk, or after the
+    chunks listed in ``cache_chunks``).
     """
     N = wl.N if n_layers is None else n_layers
     if use_timesteps is None:
@@ -89,7 +90,7 @@ def run_stream_both(wl, n_chunks, steps=1, device="cuda:0", base_seed=0, use_tim
             oc = ora.caches[layer][0]
             res["state_equal"] &= gpu.state(layer, 0) == oc.state()
             res["slot_map_equal"] &= bool(np.array_equal(gpu.slot_map(layer, 0), oc.slot_map()))
-            if check_cache:
+            if check_cache and (cache_chunks is None or chunk in cache_chunks):
                 K, V, ids = gpu.cache_logical(layer, 0)
                 want_ids = oc.slot_map()
                 live = want_ids >= 0

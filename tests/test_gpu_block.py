@@ -10,6 +10,8 @@ import numpy as np
 import pytest
 import torch
 
+import oracle
+
 from paper_2511_07399_amd import binding, workloads as wk
 from parity_util import GpuRunner, OracleRunner, max_rel_err, run_stream_both
 
@@ -117,6 +119,15 @@ def test_block_call_validation_leaves_state_untouched():
     gpu.close()
 
 
+@pytest.mark.timeout(600)
+def test_wan13b_block_long_stream():
+    """64 chunks through one 1.3B-shaped block: the window ring wraps 21 times.  Outputs, host state and slot maps
+    every chunk; cache contents and device id maps on chunks 4, 31 and 63."""
+    res = run_stream_both(wk.WORKLOADS["wan1.3b-block"], n_chunks=64, check_cache=True, cache_chunks=(4, 31, 63))
+    check(res)
+    assert len(res["x_err"]) == 64 and len(res["k_err"]) == 3
+
+
 def test_wan13b_block_first_chunks():
     """1.3B-shaped block at full size: warm-up chunks 0-2 and the first evictions (3, 4)."""
     res = run_stream_both(wk.WORKLOADS["wan1.3b-block"], n_chunks=5, check_cache=True)
@@ -140,3 +151,80 @@ def test_wan14b_block_full_size():
     wl = wk.WORKLOADS["wan14b-step"]
     res = run_stream_both(wl, n_chunks=4, n_layers=1, check_cache=False)
     check(res)
+
+
+@pytest.mark.timeout(900)
+def test_480p_geometry_staggered_batch_of_four():
+    """The batched 480p schedule at its real token counts (30 x 52 tokens per frame, chunks of 3 frames = 4680 tokens,
+    sink 1 frame + window 6 frames = 10920 keys, four streams that start one round apart) on a narrower model
+    (C 256, 2 heads) so that the oracle can follow a stream: stream 0 through warm-up, first eviction and the
+    append that wraps inside a chunk; stream 3's first chunk, which sits last in a batch of four; cache state and
+    slot maps of every stream in every round.  (The projections at the 14B width are covered, at these row
+    counts, by the sampled-row kernel tests.)"""
+    wl = wk.Workload("480p-narrow", C=256, H=2, F=512, grid_h=30, grid_w=52, frames_per_chunk=3, sink_frames=1,
+                     window_frames=6, L_t=512, B=4, N=1, steps=(1,), chunks=4)
+    gpu = GpuRunner(wl, n_streams=4)
+    ora = OracleRunner(wl, n_streams=4)
+    # streams the oracle does not follow still get their cache state from the oracle's cache class (width 1)
+    shadow = {s: oracle.RollingKVCache(wl.S, wl.W, wl.P, 1) for s in (1, 2)}
+    for rnd in range(4):
+        active = [s for s in range(4) if rnd >= s]
+        descs = [(s, (rnd - s) * wl.frames_per_chunk, wl.frames_per_chunk, 1) for s in active]
+        xs = [wk.chunk_input(wl, rnd - s, s) for s in active]
+        ts = [wk.timestep(wl, rnd - s, 0, s) for s in active]
+        xg = torch.stack(xs).to(gpu.device).contiguous()
+        gpu.denoise(xg, descs, timesteps=ts)
+        torch.cuda.synchronize()
+        for i, s in enumerate(active):
+            if s in shadow:
+                shadow[s].append_evict(np.zeros((wl.L, 1)), np.zeros((wl.L, 1)))
+                want = shadow[s]
+            else:
+                xo = ora.denoise(xs[i].double().numpy(), descs[i], timestep=ts[i])
+                err = max_rel_err(xg[i].cpu().numpy(), xo)
+                assert err <= TOL_X, (rnd, s, err)
+                want = ora.caches[0][s]
+            assert gpu.state(0, s) == want.state(), (rnd, s)
+            assert np.array_equal(gpu.slot_map(0, s), want.slot_map()), (rnd, s)
+    # stream 0 has evicted and wrapped: its cached K/V against the oracle's
+    K, V, ids = gpu.cache_logical(0, 0)
+    oc = ora.caches[0][0]
+    assert oc.state()["evicted"] > 0
+    want_ids = oc.slot_map()
+    assert np.array_equal(ids, want_ids)
+    ko, vo = oc.slot_contents()
+    assert max_rel_err(K, ko) <= TOL_KV and max_rel_err(V, vo) <= TOL_KV
+    gpu.close()
+
+
+@pytest.mark.timeout(900)
+def test_wan14b_480p_block_staggered_streams():
+    """One block of the batched 480p workload at full width (C 5120, 40 heads, FFN 13824; 4680 tokens per chunk,
+    up to 10920 keys): four rounds in which streams 0 .. 3 join one after the other, the last with all four in one
+    call (18720 rows).  The oracle follows stream 0 through warm-up, its first eviction, whose append wraps inside
+    the chunk, and one steady-state chunk; the other streams' cache state is checked against the oracle's cache
+    class."""
+    wl = wk.WORKLOADS["wan14b-480p-b4"]
+    gpu = GpuRunner(wl, n_layers=1, n_streams=4)
+    ora = OracleRunner(wl, n_layers=1, n_streams=1)
+    shadow = {s: oracle.RollingKVCache(wl.S, wl.W, wl.P, 1) for s in (1, 2, 3)}
+    for rnd in range(4):
+        active = [s for s in range(4) if rnd >= s]
+        descs = [(s, (rnd - s) * wl.frames_per_chunk, wl.frames_per_chunk, 1) for s in active]
+        xs = [wk.chunk_input(wl, rnd - s, s) for s in active]
+        ts = [wk.timestep(wl, rnd - s, 0, s) for s in active]
+        xg = torch.stack(xs).to(gpu.device).contiguous()
+        gpu.denoise(xg, descs, timesteps=ts)
+        torch.cuda.synchronize()
+        xo = ora.denoise(xs[0].double().numpy(), descs[0], timestep=ts[0])
+        err = max_rel_err(xg[0].cpu().numpy(), xo)
+        print("round %d: stream 0 max rel err %.3e" % (rnd, err), flush=True)
+        assert err <= TOL_X, (rnd, err)
+        for s in active:
+            if s in shadow:
+                shadow[s].append_evict(np.zeros((wl.L, 1)), np.zeros((wl.L, 1)))
+            want = shadow[s] if s in shadow else ora.caches[0][0]
+            assert gpu.state(0, s) == want.state(), (rnd, s)
+            assert np.array_equal(gpu.slot_map(0, s), want.slot_map()), (rnd, s)
+    assert ora.caches[0][0].state()["evicted"] > 0
+    gpu.close()
