@@ -11,6 +11,7 @@ What it follows (StreamDiffusionV2):
     (Section 1 "Efficiency objectives", Section 5.1 implementation details);
   * the sink-token-guided rolling KV cache with frame-by-frame updates
     (abstract; Section 1; Appendix D, rolling-KV-cache figure);
+  * the adaptive sink refresh and the RoPE refresh (Section 4.1), in ``refresh.py``;
   * a causal DiT of the Wan 2.1 / CausVid lineage (Section 5.1 "Models") whose
     per-layer cost is 24 b L_q C^2 + 4 b L_q L_kv C (Appendix B).
 
@@ -26,6 +27,13 @@ same code can run in float32 (a test bounds the difference).
 """
 
 from .kv_cache import RollingKVCache  # noqa: F401
+from .refresh import (  # noqa: F401
+    sink_similarity,
+    refresh_sink,
+    adaptive_sink_update,
+    rope_refresh_frame,
+    rotate_keys,
+)
 from .dit_block import (  # noqa: F401
     layer_norm,
     rms_norm,
