@@ -194,6 +194,46 @@ int32_t sdv2_kv_cache_device_ptrs(const sdv2_kv_cache* cache, int32_t layer, int
                                   void** k_dev, void** vt_dev, int64_t** ids_dev, int32_t* cap);
 
 /* ------------------------------------------------------------------------------------------------
+ * Adaptive sink refresh and RoPE refresh (Section 4.1, "Adaptive sink and RoPE refresh").
+ *
+ * The section defines, for sinks s_1 .. s_m and a new chunk embedding h_t:  alpha_i = cos(h_t, s_i);  s_i is kept
+ * when alpha_i >= tau and replaced by h_t otherwise; and, past a frame index T_reset, the rotary phase of frame t
+ * is that of frame t - T_reset.  It does not say what the vectors are; this library takes, per (layer, stream):
+ *   s_i  = sink frame i of the cache (tokens_per_frame slots starting at slot i * tokens_per_frame;
+ *          m = sink_tokens / tokens_per_frame),
+ *   h_t  = one frame of the most recent append, frame_back = 0 being its last frame,
+ *   cos  = cosine of the two frames' cached VALUE rows, each flattened to tokens_per_frame * C numbers (values
+ *          carry no rotary phase),
+ *   s_i <- h_t = a copy of that frame's cached keys, values and token ids into the sink frame's slots (the keys
+ *          keep the phase of the frame they came from; until that frame leaves the window its tokens are
+ *          resident twice).
+ * The comparison with tau is the caller's: read alpha back and call sdv2_kv_cache_refresh_sink for the sinks to
+ * replace, so that the host-side slot map stays a function of the call history.  The frame index handed to the
+ * block (chunk_desc.frame_pos0) is the caller's as well; when it is lowered by delta frames the cached keys are
+ * moved along with sdv2_kv_cache_rotate_keys, which keeps every query/key phase difference.
+ *
+ * sdv2_sink_similarity: alpha_dev (dev fp32 [m]) <- alpha_i.  fp32 partial sums per workgroup, added in double in a
+ *   fixed order (deterministic).  Workspace: sdv2_sink_similarity_workspace_bytes(cache), 256-byte aligned.
+ *   Errors: SDV2_BAD_STATE when the sink is not filled, nothing has been appended, or the frame asked for was
+ *   itself stored in the sink; SDV2_INVALID_ARG for frame_back outside the latest append.
+ * sdv2_kv_cache_refresh_sink: the copy, and the slot map's sink entries.  It closes the chunk: a later append with
+ *   advance = 0 is refused (SDV2_BAD_STATE) until the next advancing append, because a repeated denoising step
+ *   would rewrite the source frame but not its copy.  Same errors, plus sink_frame outside [0, m).
+ * sdv2_kv_cache_rotate_keys: every resident key (sink and window) of the (layer, stream) cache is turned, in
+ *   place, by -delta_frames * base^(-j / n_f) in each of the n_f = 22 leading pairs of a head (the frame axis of
+ *   the 3-axis rotary embedding): a key cached at frame f becomes the key of frame f - delta_frames, rounded to
+ *   bf16 again.  delta_frames may be negative.  Values, ids and all counters are untouched.
+ * None of the three synchronises or allocates.
+ * ------------------------------------------------------------------------------------------------ */
+size_t sdv2_sink_similarity_workspace_bytes(const sdv2_kv_cache* cache);
+int32_t sdv2_sink_similarity(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int32_t frame_back,
+                             float* alpha_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+int32_t sdv2_kv_cache_refresh_sink(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int32_t sink_frame,
+                                   int32_t frame_back, void* hip_stream);
+int32_t sdv2_kv_cache_rotate_keys(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int32_t delta_frames,
+                                  float rope_base, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Text keys/values of the cross-attention (per prompt and layer; off the per-chunk path: prompt
  * changes are events, Section 1 "Vision quality objectives").
  *   K_t = RMSNorm(ctx W_ck^T + b_ck) g_ck,   V_t = ctx W_cv^T + b_cv

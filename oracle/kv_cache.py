@@ -185,7 +185,7 @@ class RollingKVCache:
         """Counters compared bit for bit with the library's host-side state."""
         win_fill = len(self.window_ids)
         if win_fill:
-            oldest_slot = self.slot_ids.index(self.window_ids[0])
+            oldest_slot = self.slot_ids.index(self.window_ids[0], self.S)    # the window copy: a refreshed sink may hold the id too
         else:
             oldest_slot = -1
         if len(self.sink_ids) < self.S:

@@ -63,7 +63,8 @@ class CacheState(C.Structure):
 EXPORTS = (
     "sdv2_last_error", "sdv2_version", "sdv2_kv_cache_bytes", "sdv2_kv_cache_init", "sdv2_kv_cache_destroy",
     "sdv2_kv_cache_reset", "sdv2_kv_cache_append_evict", "sdv2_kv_cache_state", "sdv2_kv_cache_slot_map",
-    "sdv2_kv_cache_device_ptrs", "sdv2_text_kv_bytes", "sdv2_text_kv_workspace_bytes", "sdv2_text_kv_prepare",
+    "sdv2_kv_cache_device_ptrs", "sdv2_sink_similarity_workspace_bytes", "sdv2_sink_similarity",
+    "sdv2_kv_cache_refresh_sink", "sdv2_kv_cache_rotate_keys", "sdv2_text_kv_bytes", "sdv2_text_kv_workspace_bytes", "sdv2_text_kv_prepare",
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
     "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
@@ -98,6 +99,11 @@ def load_library():
     lib.sdv2_kv_cache_slot_map.argtypes = [vp, i32, i32, C.POINTER(C.c_int64)]
     lib.sdv2_kv_cache_device_ptrs.argtypes = [vp, i32, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                               C.POINTER(i32)]
+    lib.sdv2_sink_similarity_workspace_bytes.restype = sz
+    lib.sdv2_sink_similarity_workspace_bytes.argtypes = [vp]
+    lib.sdv2_sink_similarity.argtypes = [vp, i32, i32, i32, vp, vp, sz, vp]
+    lib.sdv2_kv_cache_refresh_sink.argtypes = [vp, i32, i32, i32, i32, vp]
+    lib.sdv2_kv_cache_rotate_keys.argtypes = [vp, i32, i32, i32, C.c_float, vp]
     lib.sdv2_text_kv_bytes.restype = sz
     lib.sdv2_text_kv_bytes.argtypes = [C.POINTER(ModelCfg)]
     lib.sdv2_text_kv_workspace_bytes.restype = sz
@@ -227,6 +233,25 @@ def kv_cache_append_evict(handle, layer, stream_id, k, v, advance=True):
     _dev(v, torch.bfloat16)
     _check(_lib.sdv2_kv_cache_append_evict(handle, layer, stream_id, _ptr(k), _ptr(v), k.shape[0], int(advance),
                                            _stream()))
+
+
+def sink_similarity_workspace_bytes(handle):
+    return int(_lib.sdv2_sink_similarity_workspace_bytes(handle))
+
+
+def sink_similarity(handle, layer, stream_id, alpha, workspace, frame_back=0):
+    """alpha (device fp32 [sink frames]) <- cos(frame `frame_back` of the latest append, sink frame i)."""
+    _dev(alpha, torch.float32)
+    _check(_lib.sdv2_sink_similarity(handle, layer, stream_id, frame_back, _ptr(alpha), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def kv_cache_refresh_sink(handle, layer, stream_id, sink_frame, frame_back=0):
+    _check(_lib.sdv2_kv_cache_refresh_sink(handle, layer, stream_id, sink_frame, frame_back, _stream()))
+
+
+def kv_cache_rotate_keys(handle, layer, stream_id, delta_frames, rope_base=10000.0):
+    _check(_lib.sdv2_kv_cache_rotate_keys(handle, layer, stream_id, delta_frames, rope_base, _stream()))
 
 
 def kv_cache_state(handle, layer, stream_id):

@@ -87,7 +87,10 @@ struct sdv2_kv_cache {
     unsigned char* base;
     size_t k_bytes, ids_bytes, unit_bytes;   // per (layer, stream)
     std::vector<int64_t> total;    // [layer * n_streams + stream]
-    std::vector<int32_t> last_n;   // size of the most recent advancing append (0: none)
+    std::vector<int32_t> last_n;   // size of the most recent advancing append (0: none); negated once a sink
+                                   // refresh has closed that chunk (advance = 0 is then refused)
+    std::vector<std::vector<int64_t>> sink_ids;   // per (layer, stream): ids held by the sink slots after a
+                                                  // refresh (empty: the first S tokens, the closed form)
 };
 
 namespace {
@@ -167,6 +170,7 @@ int32_t sdv2_kv_cache_init(const sdv2_cache_cfg* cfg, void* dev_storage, size_t 
     c->base = static_cast<unsigned char*>(dev_storage);
     c->total.assign((size_t)cfg->n_layers * cfg->n_streams, 0);
     c->last_n.assign((size_t)cfg->n_layers * cfg->n_streams, 0);
+    c->sink_ids.assign((size_t)cfg->n_layers * cfg->n_streams, std::vector<int64_t>());
     *out = c;
     return SDV2_OK;
 }
@@ -182,6 +186,7 @@ int32_t sdv2_kv_cache_reset(sdv2_kv_cache* cache, int32_t stream_id) {
     for (int l = 0; l < cache->cfg.n_layers; ++l) {
         cache->total[(size_t)l * cache->cfg.n_streams + stream_id] = 0;
         cache->last_n[(size_t)l * cache->cfg.n_streams + stream_id] = 0;
+        cache->sink_ids[(size_t)l * cache->cfg.n_streams + stream_id].clear();
     }
     return SDV2_OK;
 }
@@ -210,7 +215,8 @@ int32_t sdv2_kv_cache_slot_map(const sdv2_kv_cache* cache, int32_t layer, int32_
     const int64_t total = cache->total[(size_t)layer * cache->cfg.n_streams + stream_id];
     for (int i = 0; i < S + W; ++i) slot_map_out[i] = -1;
     const int64_t sink_end = total < S ? total : S;
-    for (int64_t g = 0; g < sink_end; ++g) slot_map_out[g] = g;
+    const std::vector<int64_t>& refreshed = cache->sink_ids[(size_t)layer * cache->cfg.n_streams + stream_id];
+    for (int64_t g = 0; g < sink_end; ++g) slot_map_out[g] = refreshed.empty() ? g : refreshed[(size_t)g];
     int64_t first = total - W;
     if (first < S) first = S;
     for (int64_t g = first; g < total; ++g) slot_map_out[slot_of_host(g, S, W)] = g;
@@ -262,6 +268,127 @@ int32_t sdv2_kv_cache_append_evict(sdv2_kv_cache* cache, int32_t layer, int32_t 
         cache->last_n[idx] = old_last;
         return hip_fail(e, "append kernel");
     }
+    return SDV2_OK;
+}
+
+// ------------------------------------------------------------------------------------------ sink / RoPE refresh
+namespace {
+// First slot of frame `frame_back` (0 = last) of the most recent append; < 0 with an error set.
+int32_t latest_frame_slot(const sdv2_kv_cache* cache, size_t idx, int32_t frame_back, int* slot0) {
+    const sdv2_cache_cfg& cf = cache->cfg;
+    const int P = cf.tokens_per_frame;
+    const int last = cache->last_n[idx] < 0 ? -cache->last_n[idx] : cache->last_n[idx];
+    if (last == 0) return fail(SDV2_BAD_STATE, "nothing has been appended yet");
+    if (frame_back < 0 || frame_back >= last / P)
+        return fail(SDV2_INVALID_ARG, "frame_back %d outside the latest append of %d frames", frame_back, last / P);
+    const int64_t g0 = cache->total[idx] - (int64_t)(frame_back + 1) * P;
+    if (g0 < cf.sink_tokens) return fail(SDV2_BAD_STATE, "that frame was stored in the sink itself");
+    *slot0 = slot_of_host(g0, cf.sink_tokens, cf.window_tokens);
+    return SDV2_OK;
+}
+}  // namespace
+
+size_t sdv2_sink_similarity_workspace_bytes(const sdv2_kv_cache* cache) {
+    if (!cache) return 0;
+    const int m = cache->cfg.sink_tokens / cache->cfg.tokens_per_frame;
+    return align_up((size_t)(m > 0 ? m : 1) * sink_similarity_blocks(cache->cfg.n_heads) * 3 * sizeof(float), 256);
+}
+
+int32_t sdv2_sink_similarity(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int32_t frame_back,
+                             float* alpha_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    int32_t rc = check_layer_stream(cache, layer, stream_id);
+    if (rc) return rc;
+    if (!alpha_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "alpha / workspace is null");
+    const sdv2_cache_cfg& cf = cache->cfg;
+    const size_t idx = (size_t)layer * cf.n_streams + stream_id;
+    const int m = cf.sink_tokens / cf.tokens_per_frame;
+    if (m == 0) return fail(SDV2_BAD_STATE, "the cache has no sink");
+    if (cache->total[idx] < cf.sink_tokens) return fail(SDV2_BAD_STATE, "the sink is not filled yet");
+    if (workspace_bytes < sdv2_sink_similarity_workspace_bytes(cache))
+        return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes,
+                    sdv2_sink_similarity_workspace_bytes(cache));
+    int src0 = 0;
+    rc = latest_frame_slot(cache, idx, frame_back, &src0);
+    if (rc) return rc;
+    AppendStream st = append_stream(cache, layer, stream_id, 0, 0);
+    SinkSimArgs a;
+    a.vt = st.vt_cache;
+    a.H = cf.n_heads;
+    a.cap = cache->cap;
+    a.P = cf.tokens_per_frame;
+    a.src0 = src0;
+    a.m = m;
+    a.partial = static_cast<float*>(workspace_dev);
+    a.alpha = alpha_dev;
+    hipError_t e = launch_sink_similarity(a, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "sink similarity kernel");
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_refresh_sink(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int32_t sink_frame,
+                                   int32_t frame_back, void* hip_stream) {
+    int32_t rc = check_layer_stream(cache, layer, stream_id);
+    if (rc) return rc;
+    const sdv2_cache_cfg& cf = cache->cfg;
+    const size_t idx = (size_t)layer * cf.n_streams + stream_id;
+    const int P = cf.tokens_per_frame;
+    const int m = cf.sink_tokens / P;
+    if (sink_frame < 0 || sink_frame >= m) return fail(SDV2_INVALID_ARG, "sink_frame %d out of range (%d sink frames)", sink_frame, m);
+    if (cache->total[idx] < cf.sink_tokens) return fail(SDV2_BAD_STATE, "the sink is not filled yet");
+    int src0 = 0;
+    rc = latest_frame_slot(cache, idx, frame_back, &src0);
+    if (rc) return rc;
+    AppendStream st = append_stream(cache, layer, stream_id, 0, 0);
+    SinkCopyArgs a;
+    a.k = st.k_cache;
+    a.vt = st.vt_cache;
+    a.ids = st.ids;
+    a.H = cf.n_heads;
+    a.cap = cache->cap;
+    a.P = P;
+    a.src0 = src0;
+    a.dst0 = sink_frame * P;
+    hipError_t e = launch_refresh_sink(a, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "sink refresh kernel");
+    std::vector<int64_t>& ids = cache->sink_ids[idx];
+    if (ids.empty()) {
+        ids.resize((size_t)cf.sink_tokens);
+        for (int g = 0; g < cf.sink_tokens; ++g) ids[(size_t)g] = g;
+    }
+    const int64_t g0 = cache->total[idx] - (int64_t)(frame_back + 1) * P;
+    for (int j = 0; j < P; ++j) ids[(size_t)sink_frame * P + j] = g0 + j;
+    if (cache->last_n[idx] > 0) cache->last_n[idx] = -cache->last_n[idx];      // the chunk is closed
+    return SDV2_OK;
+}
+
+int32_t sdv2_kv_cache_rotate_keys(sdv2_kv_cache* cache, int32_t layer, int32_t stream_id, int32_t delta_frames,
+                                  float rope_base, void* hip_stream) {
+    int32_t rc = check_layer_stream(cache, layer, stream_id);
+    if (rc) return rc;
+    if (!(rope_base > 1.0f)) return fail(SDV2_INVALID_ARG, "rope_base out of range");
+    const sdv2_cache_cfg& cf = cache->cfg;
+    const size_t idx = (size_t)layer * cf.n_streams + stream_id;
+    sdv2_cache_state stt;
+    rc = sdv2_kv_cache_state(cache, layer, stream_id, &stt);
+    if (rc) return rc;
+    AppendStream st = append_stream(cache, layer, stream_id, 0, 0);
+    RotateKeysArgs a;
+    a.k = st.k_cache;
+    a.H = cf.n_heads;
+    a.cap = cache->cap;
+    a.S = cf.sink_tokens;
+    a.sink_fill = stt.sink_fill;
+    a.n_slots = stt.sink_fill + stt.win_fill;
+    const int pairs = SDV2_HEAD_DIM / 2;
+    a.n_pairs = pairs - 2 * (pairs / 3);                          // the frame axis owns the leading pairs
+    for (int j = 0; j < kMaxFramePairs; ++j) {
+        const double ang = j < a.n_pairs ? -(double)delta_frames * pow((double)rope_base, -(double)j / a.n_pairs) : 0.0;
+        a.cs[j] = (float)cos(ang);
+        a.sn[j] = (float)sin(ang);
+    }
+    (void)idx;
+    hipError_t e = launch_rotate_keys(a, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "key rotation kernel");
     return SDV2_OK;
 }
 

@@ -133,6 +133,36 @@ struct PlainAppendArgs {
 };
 hipError_t launch_plain_append(const PlainAppendArgs& a, hipStream_t s);
 
+// Sink refresh and RoPE refresh of one (layer, stream) cache (Section 4.1).
+struct SinkSimArgs {
+    const bf16* vt;       // [H][128][cap]
+    int H, cap, P;        // P = tokens per frame
+    int src0;             // first slot of the frame h_t
+    int m;                // sink frames; sink frame i starts at slot i * P
+    float* partial;       // [m][blocks][3] fp32
+    float* alpha;         // [m]
+};
+int sink_similarity_blocks(int H);
+hipError_t launch_sink_similarity(const SinkSimArgs& a, hipStream_t s);
+struct SinkCopyArgs {
+    bf16* k;              // [H][cap][128]
+    bf16* vt;             // [H][128][cap]
+    long long* ids;       // [cap]
+    int H, cap, P;
+    int src0, dst0;       // first slots of the source frame and of the sink frame
+};
+hipError_t launch_refresh_sink(const SinkCopyArgs& a, hipStream_t s);
+constexpr int kMaxFramePairs = kHeadDim / 2;
+struct RotateKeysArgs {
+    bf16* k;              // [H][cap][128]
+    int H, cap, S;
+    int sink_fill;        // filled sink slots [0, sink_fill)
+    int n_slots;          // sink_fill + filled window slots [S, S + n_slots - sink_fill)
+    int n_pairs;          // leading pairs of a head that belong to the frame axis
+    float cs[kMaxFramePairs], sn[kMaxFramePairs];
+};
+hipError_t launch_rotate_keys(const RotateKeysArgs& a, hipStream_t s);
+
 // Re-layout of text K/V rows [L_t, C] into the cache layouts.
 hipError_t launch_text_relayout(const bf16* k_rows, const bf16* v_rows, bf16* kt, bf16* vtt,
                                 int L_t, int C, int H, int cap, hipStream_t s);

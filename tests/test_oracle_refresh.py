@@ -143,6 +143,24 @@ def test_refreshed_sink_is_attended_and_survives_eviction_of_its_source():
     assert not any(np.array_equal(k[i:i + P], src_k) for i in range(P, k.shape[0] - P + 1, P))
 
 
+def test_counters_ignore_the_sink_copy_of_a_window_token():
+    """The frame copied into the sink is still the oldest window frame: its id is in the slot map twice, and the
+    window's oldest slot is the one in the ring part."""
+    P, C = 4, 8
+    c = RollingKVCache(P, 2 * P, P, C)
+    g = rng(11)
+    for _ in range(3):
+        c.append_evict(g.normal(size=(P, C)), g.normal(size=(P, C)))
+    before = c.state()
+    c.append_evict(g.normal(size=(2 * P, C)), g.normal(size=(2 * P, C)))       # two frames: the window, wrapped
+    st = c.state()
+    oracle.refresh_sink(c, 0, frame_back=1)                                     # frame_back 1 = the oldest window frame
+    assert c.state() == st and st["oldest_slot"] >= c.S
+    sm = c.slot_map()
+    assert list(sm[:P]) == list(sm[st["oldest_slot"]:st["oldest_slot"] + P])
+    assert before["evicted"] == 0 and st["evicted"] == P
+
+
 def test_refresh_closes_the_chunk():
     c, hist = filled_cache()
     k, v = hist[-1]
