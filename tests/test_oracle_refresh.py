@@ -158,7 +158,7 @@ def test_counters_ignore_the_sink_copy_of_a_window_token():
     assert c.state() == st and st["oldest_slot"] >= c.S
     sm = c.slot_map()
     assert list(sm[:P]) == list(sm[st["oldest_slot"]:st["oldest_slot"] + P])
-    assert before["evicted"] == 0 and st["evicted"] == P
+    assert before["evicted"] == 0 and st["evicted"] == 2 * P
 
 
 def test_refresh_closes_the_chunk():
