@@ -75,6 +75,10 @@ def main():
             "gemm_tflops": round(m2["gemm_tflops"], 1), "attn_tflops": round(m2["attn_tflops"], 1),
             "kernels": m2["kernels"]}}
 
+    if not args.no_also:
+        also = dict(also or {})
+        also["refresh"] = measure_refresh(args.workload)
+
     # ---- oracle on the host cores (a reported baseline, not the target)
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -212,6 +216,54 @@ def measure(workload, steps, warmup, copy_calibration):
     return {"ms_per_step": ms_per_step, "wall_ms": wall_ms, "kernels": kernels, "roofline": roofline,
             "step_flops": step_flops, "gemm_tflops": gemm_tflops, "attn_tflops": attn_tflops, "l_kv": l_kv}
 
+
+
+def measure_refresh(workload, reps=20):
+    """The three cache-refresh operations (sink similarity, sink copy, key move) on ONE (layer, stream) cache of the
+    workload's geometry at steady state: average launch time over `reps` launches and the rate on their
+    algorithmic bytes (similarity: the value rows of two frames per sink; copy: keys and values of a frame read and
+    written; move: the 44 rotated elements of every head of every resident key read and written)."""
+    import torch
+    from paper_2511_07399_amd import binding, workloads as wk
+    wl = wk.WORKLOADS[workload]
+    dev = "cuda:0"
+    ccfg = binding.cache_cfg(1, 1, wl.H, wl.P, wl.S, wl.W)
+    storage = torch.zeros(binding.kv_cache_bytes(ccfg), dtype=torch.uint8, device=dev)
+    h = binding.kv_cache_init(ccfg, storage)
+    gen = torch.Generator().manual_seed(5)
+    n = wl.frames_per_chunk * wl.P
+    binding.kv_cache_append_evict(h, 0, 0, torch.randn(wl.S, wl.C, generator=gen).to(dev, torch.bfloat16),
+                                  torch.randn(wl.S, wl.C, generator=gen).to(dev, torch.bfloat16), True)
+    for _ in range(wl.W // n + 1):
+        binding.kv_cache_append_evict(h, 0, 0, torch.randn(n, wl.C, generator=gen).to(dev, torch.bfloat16),
+                                      torch.randn(n, wl.C, generator=gen).to(dev, torch.bfloat16), True)
+    m = wl.S // wl.P
+    alpha = torch.empty(m, dtype=torch.float32, device=dev)
+    ws = torch.empty(binding.sink_similarity_workspace_bytes(h), dtype=torch.uint8, device=dev)
+
+    def timed(fn):
+        for i in range(3):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    frame = wl.P * wl.C * 2
+    ops = {
+        "sink similarity": (timed(lambda i: binding.sink_similarity(h, 0, 0, alpha, ws, 0)), 2 * frame * m),
+        "sink copy": (timed(lambda i: binding.kv_cache_refresh_sink(h, 0, 0, 0, 0)), 4 * frame),
+        "key move": (timed(lambda i: binding.kv_cache_rotate_keys(h, 0, 0, 3 if i % 2 == 0 else -3)),
+                     2 * (wl.S + wl.W) * wl.H * 44 * 2),
+    }
+    binding.kv_cache_destroy(h)
+    return {"cache": "%s: one layer, one stream, %d-token frames, sink %d + window %d tokens, C %d"
+                     % (wl.name, wl.P, wl.S, wl.W, wl.C),
+            "ops": {k: {"us": round(us, 2), "bytes": b, "GB/s": round(b / (us * 1e-6) / 1e9, 1)} for k, (us, b) in ops.items()}}
 
 
 def load_traffic(workload, launch_site):

@@ -18,14 +18,31 @@ __global__ __launch_bounds__(kSimBlock) void sink_similarity_partial_kernel(Sink
     const int sink0 = sink * a.P;
     const int rows = a.H * kHeadDim;
     float dot = 0.0f, hh = 0.0f, ss = 0.0f;
+    // Four consecutive slots that start at a multiple of four sit in four consecutive columns (the permutation
+    // moves whole groups of four), so frames that start at multiples of four are read 8 bytes at a time.
+    const bool quads = (a.P % 4 == 0) && (a.src0 % 4 == 0);
     for (int row = blockIdx.x; row < rows; row += gridDim.x) {
         const bf16* v = a.vt + (size_t)row * a.cap;
-        for (int j = threadIdx.x; j < a.P; j += kSimBlock) {
-            const float x = (float)v[vt_column(a.src0 + j)];
-            const float y = (float)v[vt_column(sink0 + j)];
-            dot += x * y;
-            hh += x * x;
-            ss += y * y;
+        if (quads) {
+            for (int q = threadIdx.x; q < a.P / 4; q += kSimBlock) {
+                const bf16x4 x = *reinterpret_cast<const bf16x4*>(v + vt_column(a.src0 + 4 * q));
+                const bf16x4 y = *reinterpret_cast<const bf16x4*>(v + vt_column(sink0 + 4 * q));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float xf = (float)x[e], yf = (float)y[e];
+                    dot += xf * yf;
+                    hh += xf * xf;
+                    ss += yf * yf;
+                }
+            }
+        } else {
+            for (int j = threadIdx.x; j < a.P; j += kSimBlock) {
+                const float x = (float)v[vt_column(a.src0 + j)];
+                const float y = (float)v[vt_column(sink0 + j)];
+                dot += x * y;
+                hh += x * x;
+                ss += y * y;
+            }
         }
     }
     __shared__ float red[3][kSimBlock / kWave];
@@ -46,18 +63,23 @@ __global__ __launch_bounds__(kSimBlock) void sink_similarity_partial_kernel(Sink
     }
 }
 
-// alpha_i = dot / sqrt(|h|^2 |s_i|^2), 0 when a norm is 0; the partial sums are added in double, in block order.
-__global__ void sink_similarity_final_kernel(SinkSimArgs a, int n_blocks) {
-    const int sink = blockIdx.x * blockDim.x + threadIdx.x;
-    if (sink >= a.m) return;
-    double dot = 0.0, hh = 0.0, ss = 0.0;
-    for (int b = 0; b < n_blocks; ++b) {
+// alpha_i = dot / sqrt(|h|^2 |s_i|^2), 0 when a norm is 0.  One wave per sink: lane l adds the partial sums of
+// workgroups l, l + 64, ... in double, then the lanes are combined by a fixed butterfly.
+__global__ __launch_bounds__(kWave) void sink_similarity_final_kernel(SinkSimArgs a, int n_blocks) {
+    const int sink = blockIdx.x;
+    const int lane = threadIdx.x;
+    double acc[3] = {0.0, 0.0, 0.0};
+    for (int b = lane; b < n_blocks; b += kWave) {
         const float* p = a.partial + ((size_t)sink * n_blocks + b) * 3;
-        dot += (double)p[0];
-        hh += (double)p[1];
-        ss += (double)p[2];
+        acc[0] += (double)p[0];
+        acc[1] += (double)p[1];
+        acc[2] += (double)p[2];
     }
-    a.alpha[sink] = (hh > 0.0 && ss > 0.0) ? (float)(dot / sqrt(hh * ss)) : 0.0f;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) acc[c] += __shfl_xor(acc[c], off, kWave);
+    if (lane == 0) a.alpha[sink] = (acc[1] > 0.0 && acc[2] > 0.0) ? (float)(acc[0] / sqrt(acc[1] * acc[2])) : 0.0f;
 }
 
 // s_i <- h_t: the P key rows, value columns and token ids of the frame at slot src0 are copied to the sink frame at
@@ -65,7 +87,7 @@ __global__ void sink_similarity_final_kernel(SinkSimArgs a, int n_blocks) {
 // rows of V^T (P columns each) and, in the first of them, the ids.
 __global__ __launch_bounds__(256) void refresh_sink_kernel(SinkCopyArgs a, int k_blocks) {
     if ((int)blockIdx.x < k_blocks) {
-        // one wave per (head, token): 16 lanes x 16 bytes
+        // sixteen lanes per (head, token): 16 bytes each
         const int item = blockIdx.x * 16 + (threadIdx.x >> 4);
         if (item >= a.H * a.P) return;
         const int h = item / a.P, j = item - h * a.P;
@@ -114,7 +136,7 @@ __global__ __launch_bounds__(256) void rotate_keys_kernel(RotateKeysArgs a) {
 
 int sink_similarity_blocks(int H) {
     const int rows = H * kHeadDim;
-    return rows < 512 ? rows : 512;
+    return rows < 1024 ? rows : 1024;
 }
 
 hipError_t launch_sink_similarity(const SinkSimArgs& a, hipStream_t s) {
@@ -122,7 +144,7 @@ hipError_t launch_sink_similarity(const SinkSimArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(sink_similarity_partial_kernel, dim3(nb, a.m), dim3(kSimBlock), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(sink_similarity_final_kernel, dim3((a.m + 63) / 64), dim3(64), 0, s, a, nb);
+    hipLaunchKernelGGL(sink_similarity_final_kernel, dim3(a.m), dim3(kWave), 0, s, a, nb);
     return hipGetLastError();
 }
 
