@@ -12,6 +12,7 @@ What it follows (StreamDiffusionV2):
   * the sink-token-guided rolling KV cache with frame-by-frame updates
     (abstract; Section 1; Appendix D, rolling-KV-cache figure);
   * the adaptive sink refresh and the RoPE refresh (Section 4.1), in ``refresh.py``;
+  * the motion-aware noise scheduler (Section 4.1), in ``motion.py``;
   * a causal DiT of the Wan 2.1 / CausVid lineage (Section 5.1 "Models") whose
     per-layer cost is 24 b L_q C^2 + 4 b L_q L_kv C (Appendix B).
 
@@ -33,6 +34,12 @@ from .refresh import (  # noqa: F401
     adaptive_sink_update,
     rope_refresh_frame,
     rotate_keys,
+)
+from .motion import (  # noqa: F401
+    motion_intensity,
+    normalized_motion,
+    noise_rate,
+    MotionNoiseScheduler,
 )
 from .dit_block import (  # noqa: F401
     layer_norm,
