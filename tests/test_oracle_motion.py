@@ -54,8 +54,8 @@ def test_noise_rate_formula_and_limits():
     assert oracle.noise_rate(0.7, 0.8, 0.3, 0.2, 0.9) < oracle.noise_rate(0.7, 0.1, 0.3, 0.2, 0.9)
     # the rate stays inside [s_min, s_max] when it starts there
     for dh in (0.0, 0.3, 1.0):
-        assert 0.2 <= oracle.noise_rate(0.2, dh, 0.4, 0.2, 0.9) <= 0.9
-        assert 0.2 <= oracle.noise_rate(0.9, dh, 0.4, 0.2, 0.9) <= 0.9
+        assert 0.2 - 1e-15 <= oracle.noise_rate(0.2, dh, 0.4, 0.2, 0.9) <= 0.9 + 1e-15
+        assert 0.2 - 1e-15 <= oracle.noise_rate(0.9, dh, 0.4, 0.2, 0.9) <= 0.9 + 1e-15
 
 
 def test_static_stream_converges_geometrically_to_s_max():
