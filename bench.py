@@ -78,6 +78,7 @@ def main():
     if not args.no_also:
         also = dict(also or {})
         also["refresh"] = measure_refresh(args.workload)
+        also["motion"] = measure_motion()
 
     # ---- oracle on the host cores (a reported baseline, not the target)
     cpu_baseline = None
@@ -264,6 +265,37 @@ def measure_refresh(workload, reps=20):
     return {"cache": "%s: one layer, one stream, %d-token frames, sink %d + window %d tokens, C %d"
                      % (wl.name, wl.P, wl.S, wl.W, wl.C),
             "ops": {k: {"us": round(us, 2), "bytes": b, "GB/s": round(b / (us * 1e-6) / 1e9, 1)} for k, (us, b) in ops.items()}}
+
+
+def measure_motion(reps=20):
+    """The motion-aware noise scheduler update (frame differences + the rate recurrence) on 512 x 512 latents
+    (16 x 64 x 64 fp32 per frame) for one and for four frames per call; algorithmic bytes: each frame and its
+    predecessor read once."""
+    import torch
+    from paper_2511_07399_amd import binding
+    dev = "cuda:0"
+    n = 16 * 64 * 64
+    cfg = binding.motion_cfg(3, 1.0, 0.3, 0.1, 0.9, 0.5)
+    state = torch.empty(binding.motion_state_bytes(cfg), dtype=torch.uint8, device=dev)
+    binding.motion_init(cfg, state)
+    out = {}
+    for T in (1, 4):
+        frames = torch.randn(T, n, device=dev)
+        prev = torch.randn(n, device=dev)
+        o = [torch.empty(T, dtype=torch.float32, device=dev) for _ in range(3)]
+        for _ in range(3):
+            binding.motion_update(cfg, state, frames, prev, *o)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            binding.motion_update(cfg, state, frames, prev, *o)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        b = 2 * T * n * 4
+        out["%d frame(s) of 16x64x64 fp32" % T] = {"us": round(us, 2), "bytes": b, "GB/s": round(b / (us * 1e-6) / 1e9, 1)}
+    return out
 
 
 def load_traffic(workload, launch_site):

@@ -234,6 +234,38 @@ int32_t sdv2_kv_cache_rotate_keys(sdv2_kv_cache* cache, int32_t layer, int32_t s
                                   float rope_base, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Motion-aware noise scheduler (Section 4.1, "Motion-aware noise scheduler"), in the paper's notation:
+ *   d_t    = sqrt( ||v_t - v_{t-1}||_2^2 / (C H W) )                      v_t: latent frame, C H W = frame_elems
+ *   dhat_t = clip( max_{i in {t-k .. t}} d_i / sigma, 0, 1 )
+ *   s_t    = lambda [ s_max - (s_max - s_min) dhat_t ] + (1 - lambda) s_{t-1}
+ * Readings: the first frame of a stream has d = 0; the window is cut at the start of the stream; s before the
+ * first frame is cfg.s_init.
+ *
+ * The recurrence lives in a small device buffer `state_dev` (sdv2_motion_state_bytes(cfg) bytes, 16-byte aligned,
+ * one per stream, owned by the caller): sdv2_motion_init sets s = s_init and an empty window (one small kernel);
+ * sdv2_motion_update consumes n_frames (1 .. 16) consecutive frames `frames_dev` (dev fp32 [n_frames][frame_elems])
+ * and writes d_t, dhat_t and s_t of each to three dev fp32 [n_frames] arrays.  `prev_frame_dev` is the frame that
+ * precedes frames_dev[0] (the last frame of the previous call), or NULL at the start of a stream.  fp32 arithmetic,
+ * the sums of squares as fp32 partial sums per workgroup added in double in a fixed order (deterministic).
+ * Calls on the same state must be ordered on one stream.  No allocation, no synchronisation.
+ * Errors: bad cfg (k < 0 or > 1023, sigma <= 0, lambda outside (0, 1), s_min > s_max), null pointers, n_frames
+ * outside 1 .. 16, frame_elems <= 0: SDV2_INVALID_ARG; state too small: SDV2_WORKSPACE_TOO_SMALL.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct sdv2_motion_cfg {
+    uint32_t struct_size;
+    int32_t k;            /* window: frames t-k .. t */
+    float sigma;          /* normalising scale */
+    float lambda;         /* update rate of the moving average, 0 < lambda < 1 */
+    float s_min, s_max;   /* bounds of the noise rate */
+    float s_init;         /* s before the first frame */
+} sdv2_motion_cfg;
+size_t sdv2_motion_state_bytes(const sdv2_motion_cfg* cfg);
+int32_t sdv2_motion_init(const sdv2_motion_cfg* cfg, void* state_dev, size_t state_bytes, void* hip_stream);
+int32_t sdv2_motion_update(const sdv2_motion_cfg* cfg, void* state_dev, size_t state_bytes, const float* frames_dev,
+                           const float* prev_frame_dev, int32_t n_frames, int64_t frame_elems, float* d_out_dev,
+                           float* dhat_out_dev, float* s_out_dev, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Text keys/values of the cross-attention (per prompt and layer; off the per-chunk path: prompt
  * changes are events, Section 1 "Vision quality objectives").
  *   K_t = RMSNorm(ctx W_ck^T + b_ck) g_ck,   V_t = ctx W_cv^T + b_cv

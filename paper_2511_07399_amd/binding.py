@@ -60,11 +60,17 @@ class CacheState(C.Structure):
                 ("oldest_slot", C.c_int32), ("next_slot", C.c_int32)]
 
 
+class MotionCfg(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("k", C.c_int32), ("sigma", C.c_float), ("lam", C.c_float),
+                ("s_min", C.c_float), ("s_max", C.c_float), ("s_init", C.c_float)]
+
+
 EXPORTS = (
     "sdv2_last_error", "sdv2_version", "sdv2_kv_cache_bytes", "sdv2_kv_cache_init", "sdv2_kv_cache_destroy",
     "sdv2_kv_cache_reset", "sdv2_kv_cache_append_evict", "sdv2_kv_cache_state", "sdv2_kv_cache_slot_map",
     "sdv2_kv_cache_device_ptrs", "sdv2_sink_similarity_workspace_bytes", "sdv2_sink_similarity",
-    "sdv2_kv_cache_refresh_sink", "sdv2_kv_cache_rotate_keys", "sdv2_text_kv_bytes", "sdv2_text_kv_workspace_bytes", "sdv2_text_kv_prepare",
+    "sdv2_kv_cache_refresh_sink", "sdv2_kv_cache_rotate_keys", "sdv2_motion_state_bytes", "sdv2_motion_init",
+    "sdv2_motion_update", "sdv2_text_kv_bytes", "sdv2_text_kv_workspace_bytes", "sdv2_text_kv_prepare",
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
     "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
@@ -104,6 +110,10 @@ def load_library():
     lib.sdv2_sink_similarity.argtypes = [vp, i32, i32, i32, vp, vp, sz, vp]
     lib.sdv2_kv_cache_refresh_sink.argtypes = [vp, i32, i32, i32, i32, vp]
     lib.sdv2_kv_cache_rotate_keys.argtypes = [vp, i32, i32, i32, C.c_float, vp]
+    lib.sdv2_motion_state_bytes.restype = sz
+    lib.sdv2_motion_state_bytes.argtypes = [C.POINTER(MotionCfg)]
+    lib.sdv2_motion_init.argtypes = [C.POINTER(MotionCfg), vp, sz, vp]
+    lib.sdv2_motion_update.argtypes = [C.POINTER(MotionCfg), vp, sz, vp, vp, i32, C.c_int64, vp, vp, vp, vp]
     lib.sdv2_text_kv_bytes.restype = sz
     lib.sdv2_text_kv_bytes.argtypes = [C.POINTER(ModelCfg)]
     lib.sdv2_text_kv_workspace_bytes.restype = sz
@@ -252,6 +262,29 @@ def kv_cache_refresh_sink(handle, layer, stream_id, sink_frame, frame_back=0):
 
 def kv_cache_rotate_keys(handle, layer, stream_id, delta_frames, rope_base=10000.0):
     _check(_lib.sdv2_kv_cache_rotate_keys(handle, layer, stream_id, delta_frames, rope_base, _stream()))
+
+
+def motion_cfg(k, sigma, lam, s_min, s_max, s_init):
+    c = MotionCfg()
+    c.struct_size = C.sizeof(MotionCfg)
+    c.k, c.sigma, c.lam, c.s_min, c.s_max, c.s_init = k, sigma, lam, s_min, s_max, s_init
+    return c
+
+
+def motion_state_bytes(cfg):
+    return int(_lib.sdv2_motion_state_bytes(C.byref(cfg)))
+
+
+def motion_init(cfg, state):
+    _check(_lib.sdv2_motion_init(C.byref(cfg), _ptr(state), state.numel() * state.element_size(), _stream()))
+
+
+def motion_update(cfg, state, frames, prev_frame, d_out, dhat_out, s_out):
+    """frames: device fp32 [T, n]; prev_frame: device fp32 [n] or None; outputs device fp32 [T]."""
+    _dev(frames, torch.float32)
+    _check(_lib.sdv2_motion_update(C.byref(cfg), _ptr(state), state.numel() * state.element_size(), _ptr(frames),
+                                   None if prev_frame is None else _ptr(prev_frame), frames.shape[0],
+                                   frames.shape[1], _ptr(d_out), _ptr(dhat_out), _ptr(s_out), _stream()))
 
 
 def kv_cache_state(handle, layer, stream_id):

@@ -392,6 +392,70 @@ int32_t sdv2_kv_cache_rotate_keys(sdv2_kv_cache* cache, int32_t layer, int32_t s
     return SDV2_OK;
 }
 
+// ------------------------------------------------------------------------------------------ motion-aware noise scheduler
+namespace {
+bool motion_cfg_ok(const sdv2_motion_cfg* c, const char** why) {
+    *why = nullptr;
+    if (!c) *why = "cfg is null";
+    else if (c->struct_size != sizeof(sdv2_motion_cfg)) *why = "cfg.struct_size mismatch";
+    else if (c->k < 0 || c->k > kMotionMaxK) *why = "k out of range";
+    else if (!(c->sigma > 0.0f)) *why = "sigma must be positive";
+    else if (!(c->lambda > 0.0f && c->lambda < 1.0f)) *why = "lambda must lie strictly between 0 and 1";
+    else if (!(c->s_min <= c->s_max)) *why = "s_min > s_max";
+    return *why == nullptr;
+}
+size_t motion_ring_floats(const sdv2_motion_cfg* c) { return align_up((size_t)c->k + 1, 16); }
+}  // namespace
+
+size_t sdv2_motion_state_bytes(const sdv2_motion_cfg* cfg) {
+    const char* why;
+    if (!motion_cfg_ok(cfg, &why)) return 0;
+    return align_up((kMotionHeaderFloats + motion_ring_floats(cfg) + (size_t)kMotionMaxFrames * kMotionBlocks) * sizeof(float), 256);
+}
+
+int32_t sdv2_motion_init(const sdv2_motion_cfg* cfg, void* state_dev, size_t state_bytes, void* hip_stream) {
+    const char* why;
+    if (!motion_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!state_dev || reinterpret_cast<uintptr_t>(state_dev) % 16) return fail(SDV2_INVALID_ARG, "state is null or not 16-byte aligned");
+    const size_t need = sdv2_motion_state_bytes(cfg);
+    if (state_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "state %zu < %zu", state_bytes, need);
+    hipError_t e = launch_motion_init(static_cast<float*>(state_dev), (int)(need / sizeof(float)), cfg->s_init,
+                                      static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "motion init kernel");
+    return SDV2_OK;
+}
+
+int32_t sdv2_motion_update(const sdv2_motion_cfg* cfg, void* state_dev, size_t state_bytes, const float* frames_dev,
+                           const float* prev_frame_dev, int32_t n_frames, int64_t frame_elems, float* d_out_dev,
+                           float* dhat_out_dev, float* s_out_dev, void* hip_stream) {
+    const char* why;
+    if (!motion_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!state_dev || !frames_dev || !d_out_dev || !dhat_out_dev || !s_out_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (state_bytes < sdv2_motion_state_bytes(cfg)) return fail(SDV2_WORKSPACE_TOO_SMALL, "state too small");
+    if (n_frames <= 0 || n_frames > kMotionMaxFrames) return fail(SDV2_INVALID_ARG, "n_frames %d outside 1 .. %d", n_frames, kMotionMaxFrames);
+    if (frame_elems <= 0) return fail(SDV2_INVALID_ARG, "frame_elems must be positive");
+    MotionArgs a;
+    a.frames = frames_dev;
+    a.prev = prev_frame_dev;
+    a.n = frame_elems;
+    a.T = n_frames;
+    a.k = cfg->k;
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(frames_dev) | reinterpret_cast<uintptr_t>(prev_frame_dev);
+    a.vec4 = (frame_elems % 4 == 0 && bits % 16 == 0) ? 1 : 0;
+    a.sigma = cfg->sigma;
+    a.lambda = cfg->lambda;
+    a.s_min = cfg->s_min;
+    a.s_max = cfg->s_max;
+    a.state = static_cast<float*>(state_dev);
+    a.partial = a.state + kMotionHeaderFloats + motion_ring_floats(cfg);
+    a.d_out = d_out_dev;
+    a.dhat_out = dhat_out_dev;
+    a.s_out = s_out_dev;
+    hipError_t e = launch_motion_update(a, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(e, "motion kernels");
+    return SDV2_OK;
+}
+
 // ------------------------------------------------------------------------------------------ dense helpers
 size_t sdv2_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t epilogue) {
     if (M <= 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 3) return 0;

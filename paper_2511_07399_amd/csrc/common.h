@@ -163,6 +163,27 @@ struct RotateKeysArgs {
 };
 hipError_t launch_rotate_keys(const RotateKeysArgs& a, hipStream_t s);
 
+// Motion-aware noise scheduler (Section 4.1).  Device state: kMotionHeaderFloats header floats (s, frame count as
+// int bits), then the ring of the last k + 1 intensities, then kMotionMaxFrames * kMotionBlocks partial sums.
+constexpr int kMotionHeaderFloats = 16;
+constexpr int kMotionBlocks = 64;
+constexpr int kMotionMaxFrames = 16;
+constexpr int kMotionMaxK = 1023;
+struct MotionArgs {
+    const float* frames;   // [T][n]
+    const float* prev;     // [n] or null: the frame before frames[0]
+    long long n;
+    int T, k, vec4;
+    float sigma, lambda, s_min, s_max;
+    float* state;
+    float* partial;        // [T][kMotionBlocks]
+    float* d_out;          // [T]
+    float* dhat_out;       // [T]
+    float* s_out;          // [T]
+};
+hipError_t launch_motion_init(float* state, int n_floats, float s_init, hipStream_t s);
+hipError_t launch_motion_update(const MotionArgs& a, hipStream_t s);
+
 // Re-layout of text K/V rows [L_t, C] into the cache layouts.
 hipError_t launch_text_relayout(const bf16* k_rows, const bf16* v_rows, bf16* kt, bf16* vtt,
                                 int L_t, int C, int H, int cap, hipStream_t s);
