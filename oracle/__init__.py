@@ -13,6 +13,7 @@ What it follows (StreamDiffusionV2):
     (abstract; Section 1; Appendix D, rolling-KV-cache figure);
   * the adaptive sink refresh and the RoPE refresh (Section 4.1), in ``refresh.py``;
   * the motion-aware noise scheduler (Section 4.1), in ``motion.py``;
+  * the SLO-aware batching scheduler (Section 4.1), in ``slo.py``;
   * a causal DiT of the Wan 2.1 / CausVid lineage (Section 5.1 "Models") whose
     per-layer cost is 24 b L_q C^2 + 4 b L_q L_kv C (Appendix B).
 
@@ -35,6 +36,7 @@ from .refresh import (  # noqa: F401
     rope_refresh_frame,
     rotate_keys,
 )
+from .slo import latency_model, frequency, pick_batch  # noqa: F401
 from .motion import (  # noqa: F401
     motion_intensity,
     normalized_motion,
