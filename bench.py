@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--workload", default="wan1.3b-step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary 14B-shaped measurement")
+    ap.add_argument("--batch-sweep", default="",
+                    help="comma-separated batch sizes (1..8): instead of the usual line, measure the step latency "
+                         "L(T, B) of the workload with B streams per call and print the table with the batch size "
+                         "the SLO-aware scheduler picks for a few target frame rates")
     ap.add_argument("--cpu-layers", type=int, default=0, help="blocks the oracle times (0: all, bounded to ~30 s)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run a plain device copy of this many MiB (read + write) three times before the timed "
@@ -58,6 +62,9 @@ def main():
     binding.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = wk.WORKLOADS[args.workload]
+    if args.batch_sweep:
+        print(json.dumps(batch_sweep(args.workload, [int(b) for b in args.batch_sweep.split(",")], args.steps, args.warmup)))
+        return
     m = measure(args.workload, args.steps, args.warmup, args.copy_calibration)
     ms_per_step, wall_ms, kernels, roofline = m["ms_per_step"], m["wall_ms"], m["kernels"], m["roofline"]
     step_flops, gemm_tflops, attn_tflops, l_kv = m["step_flops"], m["gemm_tflops"], m["attn_tflops"], m["l_kv"]
@@ -217,6 +224,35 @@ def measure(workload, steps, warmup, copy_calibration):
     return {"ms_per_step": ms_per_step, "wall_ms": wall_ms, "kernels": kernels, "roofline": roofline,
             "step_flops": step_flops, "gemm_tflops": gemm_tflops, "attn_tflops": attn_tflops, "l_kv": l_kv}
 
+
+
+def batch_sweep(workload, sizes, steps, warmup):
+    """L(T, B): the denoise-step latency of the workload with B independent streams in one call, and what
+    sdv2_slo_pick_batch makes of the table (Section 4.1, SLO-aware batching scheduler)."""
+    import dataclasses
+    from paper_2511_07399_amd import binding, workloads as wk
+    base = wk.WORKLOADS[workload]
+    table = {}
+    for b in sizes:
+        name = "%s/B%d" % (base.name, b)
+        wk.WORKLOADS[name] = dataclasses.replace(base, name=name, B=b)
+        m = measure(name, steps, warmup, 0)
+        table[b] = m["ms_per_step"]
+        print("B=%d: %.3f ms per step" % (b, table[b]), file=sys.stderr, flush=True)
+    T = base.frames_per_chunk
+    lat = {b: ms * 1e-3 for b, ms in table.items()}
+    freq = {b: b * T / lat[b] for b in lat}
+    b1 = min(lat)
+    picks = {}
+    for f_slo in (16.0, 0.9 * max(freq.values()), 2.0 * max(freq.values())):
+        for tol in (0.0, 0.05):
+            r = binding.slo_pick_batch(lat, T, f_slo, 10 ** 6, tol)
+            picks["f_slo %.1f, knee_tol %.2f" % (f_slo, tol)] = None if r is None else {"B": r[0], "f": round(r[1], 1), "meets_slo": r[2]}
+    return {"workload": base.name, "frames_per_chunk": T, "ms_per_step": {str(b): round(v, 4) for b, v in table.items()},
+            "frames_per_s": {str(b): round(freq[b], 1) for b in freq},
+            "f_over_f1": {str(b): round(freq[b] / freq[b1], 3) for b in freq},
+            "memory_bound_model_B_over_1_plus_B": {str(b): round((b / (1.0 + b)) / (b1 / (1.0 + b1)), 3) for b in freq},
+            "picks": picks}
 
 
 def measure_refresh(workload, reps=20):

@@ -266,6 +266,24 @@ int32_t sdv2_motion_update(const sdv2_motion_cfg* cfg, void* state_dev, size_t s
                            float* dhat_out_dev, float* s_out_dev, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * SLO-aware batching scheduler (Section 4.1, "SLO-aware batching scheduler").  Host-only, no GPU work.
+ * With T = frames_per_chunk frames per iteration for each of B batch slots and measured latencies L(T, B), the
+ * achieved frequency is f = B T / L(T, B); B T must not exceed the frames already collected.  Given the caller's table
+ * (batch_sizes[i], latency_s[i]), i < n (any order, sizes distinct), the call returns in *batch_out
+ *   - the SMALLEST allowed size that meets f >= f_slo and whose f is within the fraction knee_tol (0 <= knee_tol < 1)
+ *     of the best f among the sizes that meet it (the knee: beyond it a larger batch only adds latency), with
+ *     *meets_slo_out = 1;
+ *   - if no allowed size meets f_slo, the allowed size with the highest f (the smaller on ties), *meets_slo_out = 0;
+ *   - 0 if no size is allowed (fewer than the smallest B T frames collected).
+ * *frequency_out (optional) receives f of the returned size.  The latencies are the caller's measurements (e.g. of
+ * sdv2_denoise_step); the paper's model L = (A(T, B) + P_model) / (eta BW_HBM) is not assumed.
+ * Errors: null pointers, n <= 0, frames_per_chunk <= 0, a batch size < 1, a latency <= 0, knee_tol outside [0, 1).
+ * ------------------------------------------------------------------------------------------------ */
+int32_t sdv2_slo_pick_batch(const int32_t* batch_sizes, const double* latency_s, int32_t n, int32_t frames_per_chunk,
+                            double f_slo, int64_t frames_collected, double knee_tol, int32_t* batch_out,
+                            double* frequency_out, int32_t* meets_slo_out);
+
+/* ------------------------------------------------------------------------------------------------
  * Text keys/values of the cross-attention (per prompt and layer; off the per-chunk path: prompt
  * changes are events, Section 1 "Vision quality objectives").
  *   K_t = RMSNorm(ctx W_ck^T + b_ck) g_ck,   V_t = ctx W_cv^T + b_cv

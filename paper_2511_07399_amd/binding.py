@@ -70,7 +70,7 @@ EXPORTS = (
     "sdv2_kv_cache_reset", "sdv2_kv_cache_append_evict", "sdv2_kv_cache_state", "sdv2_kv_cache_slot_map",
     "sdv2_kv_cache_device_ptrs", "sdv2_sink_similarity_workspace_bytes", "sdv2_sink_similarity",
     "sdv2_kv_cache_refresh_sink", "sdv2_kv_cache_rotate_keys", "sdv2_motion_state_bytes", "sdv2_motion_init",
-    "sdv2_motion_update", "sdv2_text_kv_bytes", "sdv2_text_kv_workspace_bytes", "sdv2_text_kv_prepare",
+    "sdv2_motion_update", "sdv2_slo_pick_batch", "sdv2_text_kv_bytes", "sdv2_text_kv_workspace_bytes", "sdv2_text_kv_prepare",
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
     "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
@@ -114,6 +114,8 @@ def load_library():
     lib.sdv2_motion_state_bytes.argtypes = [C.POINTER(MotionCfg)]
     lib.sdv2_motion_init.argtypes = [C.POINTER(MotionCfg), vp, sz, vp]
     lib.sdv2_motion_update.argtypes = [C.POINTER(MotionCfg), vp, sz, vp, vp, i32, C.c_int64, vp, vp, vp, vp]
+    lib.sdv2_slo_pick_batch.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_double), i32, i32, C.c_double, C.c_int64,
+                                        C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.sdv2_text_kv_bytes.restype = sz
     lib.sdv2_text_kv_bytes.argtypes = [C.POINTER(ModelCfg)]
     lib.sdv2_text_kv_workspace_bytes.restype = sz
@@ -285,6 +287,18 @@ def motion_update(cfg, state, frames, prev_frame, d_out, dhat_out, s_out):
     _check(_lib.sdv2_motion_update(C.byref(cfg), _ptr(state), state.numel() * state.element_size(), _ptr(frames),
                                    None if prev_frame is None else _ptr(prev_frame), frames.shape[0],
                                    frames.shape[1], _ptr(d_out), _ptr(dhat_out), _ptr(s_out), _stream()))
+
+
+def slo_pick_batch(latency_s, frames_per_chunk, f_slo, frames_collected, knee_tol=0.0):
+    """latency_s: dict batch size -> seconds.  Returns None or (B*, f(B*), meets_slo)."""
+    sizes = list(latency_s)
+    n = len(sizes)
+    bs = (C.c_int32 * n)(*sizes)
+    ls = (C.c_double * n)(*[latency_s[b] for b in sizes])
+    b_out, f_out, ok = C.c_int32(), C.c_double(), C.c_int32()
+    _check(_lib.sdv2_slo_pick_batch(bs, ls, n, frames_per_chunk, f_slo, frames_collected, knee_tol, C.byref(b_out),
+                                    C.byref(f_out), C.byref(ok)))
+    return None if b_out.value == 0 else (b_out.value, f_out.value, bool(ok.value))
 
 
 def kv_cache_state(handle, layer, stream_id):

@@ -456,6 +456,51 @@ int32_t sdv2_motion_update(const sdv2_motion_cfg* cfg, void* state_dev, size_t s
     return SDV2_OK;
 }
 
+// ------------------------------------------------------------------------------------------ SLO-aware batching scheduler
+int32_t sdv2_slo_pick_batch(const int32_t* batch_sizes, const double* latency_s, int32_t n, int32_t frames_per_chunk,
+                            double f_slo, int64_t frames_collected, double knee_tol, int32_t* batch_out,
+                            double* frequency_out, int32_t* meets_slo_out) {
+    if (!batch_sizes || !latency_s || !batch_out) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (n <= 0 || frames_per_chunk <= 0) return fail(SDV2_INVALID_ARG, "n and frames_per_chunk must be positive");
+    if (!(knee_tol >= 0.0 && knee_tol < 1.0)) return fail(SDV2_INVALID_ARG, "knee_tol must lie in [0, 1)");
+    for (int i = 0; i < n; ++i)
+        if (batch_sizes[i] < 1 || !(latency_s[i] > 0.0))
+            return fail(SDV2_INVALID_ARG, "entry %d: batch size must be >= 1 and latency positive", i);
+    // f = B T / L(T, B) of the allowed sizes (B T <= frames collected)
+    int best_any = -1, best_ok = -1;
+    double f_any = 0.0, f_ok = 0.0;
+    auto freq = [&](int i) { return (double)batch_sizes[i] * frames_per_chunk / latency_s[i]; };
+    auto allowed = [&](int i) { return (int64_t)batch_sizes[i] * frames_per_chunk <= frames_collected; };
+    for (int i = 0; i < n; ++i) {
+        if (!allowed(i)) continue;
+        const double f = freq(i);
+        if (best_any < 0 || f > f_any || (f == f_any && batch_sizes[i] < batch_sizes[best_any])) {
+            best_any = i;
+            f_any = f;
+        }
+        if (f >= f_slo && (best_ok < 0 || f > f_ok)) {
+            best_ok = i;
+            f_ok = f;
+        }
+    }
+    int pick = -1, meets = 0;
+    if (best_ok >= 0) {
+        // the smallest allowed size that meets the SLO and is within knee_tol of the best such frequency
+        for (int i = 0; i < n; ++i) {
+            if (!allowed(i)) continue;
+            const double f = freq(i);
+            if (f >= f_slo && f >= (1.0 - knee_tol) * f_ok && (pick < 0 || batch_sizes[i] < batch_sizes[pick])) pick = i;
+        }
+        meets = 1;
+    } else {
+        pick = best_any;
+    }
+    *batch_out = pick < 0 ? 0 : batch_sizes[pick];
+    if (frequency_out) *frequency_out = pick < 0 ? 0.0 : freq(pick);
+    if (meets_slo_out) *meets_slo_out = meets;
+    return SDV2_OK;
+}
+
 // ------------------------------------------------------------------------------------------ dense helpers
 size_t sdv2_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t epilogue) {
     if (M <= 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 3) return 0;

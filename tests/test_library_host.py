@@ -92,3 +92,31 @@ def test_workspace_sizes_and_model_cfg_errors(lib):
     bad = binding.model_cfg(1500, 12, 8960, 32, 32, 512, 30)
     assert binding.block_workspace_bytes(bad, 1, 1024) == 0
     assert binding.block_workspace_bytes(cfg, 9, 1024) == 0          # more streams than SDV2_MAX_BATCH
+
+
+def test_slo_pick_batch_matches_the_oracle_on_random_tables():
+    """Host-only entry point: the library's choice of B* against the oracle's on 500 random latency tables."""
+    import numpy as np
+    import oracle
+    binding.load_library()
+    g = np.random.default_rng(1)
+    for trial in range(500):
+        sizes = g.permutation(g.choice(np.arange(1, 20), size=int(g.integers(1, 7)), replace=False)).tolist()
+        lat = {int(B): float(g.uniform(0.5, 3.0)) * (0.3 + B) * 1e-3 for B in sizes}
+        T = int(g.integers(1, 5))
+        f_slo = float(g.uniform(100, 3000))
+        frames = int(g.integers(0, 60))
+        tol = float(g.choice([0.0, 0.05, 0.2]))
+        got = binding.slo_pick_batch(lat, T, f_slo, frames, tol)
+        want = oracle.pick_batch(lat, T, f_slo, frames, tol)
+        if want is None:
+            assert got is None
+        else:
+            assert got[0] == want[0] and got[2] == want[2] and abs(got[1] - want[1]) <= 1e-9 * want[1]
+    for bad in (lambda: binding.slo_pick_batch({0: 1.0}, 1, 1.0, 10), lambda: binding.slo_pick_batch({1: 0.0}, 1, 1.0, 10),
+                lambda: binding.slo_pick_batch({1: 1.0}, 0, 1.0, 10), lambda: binding.slo_pick_batch({1: 1.0}, 1, 1.0, 10, 1.0)):
+        try:
+            bad()
+            assert False, "accepted a bad argument"
+        except binding.Sdv2Error as e:
+            assert e.code == binding.INVALID_ARG
