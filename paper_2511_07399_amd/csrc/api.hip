@@ -367,7 +367,6 @@ int32_t sdv2_kv_cache_rotate_keys(sdv2_kv_cache* cache, int32_t layer, int32_t s
     if (rc) return rc;
     if (!(rope_base > 1.0f)) return fail(SDV2_INVALID_ARG, "rope_base out of range");
     const sdv2_cache_cfg& cf = cache->cfg;
-    const size_t idx = (size_t)layer * cf.n_streams + stream_id;
     sdv2_cache_state stt;
     rc = sdv2_kv_cache_state(cache, layer, stream_id, &stt);
     if (rc) return rc;
@@ -386,7 +385,6 @@ int32_t sdv2_kv_cache_rotate_keys(sdv2_kv_cache* cache, int32_t layer, int32_t s
         a.cs[j] = (float)cos(ang);
         a.sn[j] = (float)sin(ang);
     }
-    (void)idx;
     hipError_t e = launch_rotate_keys(a, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return hip_fail(e, "key rotation kernel");
     return SDV2_OK;
