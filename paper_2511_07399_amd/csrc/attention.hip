@@ -38,7 +38,6 @@ namespace sdv2 {
 
 namespace {
 
-constexpr int QT = 128;       // queries per workgroup
 constexpr int KT = 64;        // keys per tile
 constexpr int D = kHeadDim;
 constexpr int K_TILE_BYTES = KT * D * 2;
@@ -69,7 +68,9 @@ __device__ __forceinline__ void load_to_lds_b128(const void* src, void* dst) {
     __builtin_amdgcn_global_load_lds(src, (lds_void_ptr)dst, 16, 0, 0);
 }
 
-__global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float scale_log2e) {
+template <int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(AttnArgs a, float scale_log2e) {
+    constexpr int QT = 32 * NW;                   // queries per workgroup: one 32-query block per wave
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     unsigned char* const k_stage = smem_raw;                          // [2][64 keys][256 B]
     unsigned char* const v_stage = smem_raw + 2 * K_TILE_BYTES;       // [2][128 d][128 B]
@@ -112,30 +113,31 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(AttnArgs a, float sca
     }
 
     // ---- direct loads.  A wave load fills 1 KB of LDS in lane order: 4 K rows or 8 V^T rows.  Wave w issues
-    // loads w, w + 4, w + 8, w + 12 of each tile; the XOR term of a lane's chunk is the same for all four.
+    // loads w, w + NW, ... of each tile; the XOR term of a lane's chunk is the same for all of them.
     const unsigned char* kbase = reinterpret_cast<const unsigned char*>(a.k[b] + (size_t)h * cap * D);
     const unsigned char* vbase = reinterpret_cast<const unsigned char*>(a.vt[b] + (size_t)h * D * cap);
-    const int k_row = 4 * wave + (lane >> 4);                                     // + 16 i
+    constexpr int LPT = 16 / NW;                  // wave loads per K tile and per V^T tile for each wave
+    const int k_row = 4 * wave + (lane >> 4);                                     // + 4 NW i
     const uint32_t k_off = (uint32_t)k_row * 256u + (uint32_t)(((lane & 15) ^ (k_row & 15)) * 16);
-    const int v_row = 8 * wave + (lane >> 3);                                     // + 32 i
+    const int v_row = 8 * wave + (lane >> 3);                                     // + 8 NW i
     const size_t v_off = (size_t)v_row * cap * 2 + (size_t)(((lane & 7) ^ ((v_row >> 1) & 7)) * 16);
     auto load_k = [&](int t, int stage) {
         const unsigned char* src = kbase + (size_t)t * K_TILE_BYTES + k_off;
         unsigned char* dst = k_stage + stage * K_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_to_lds_b128(src + i * 4096, dst + i * 4096);
+        for (int i = 0; i < LPT; ++i) load_to_lds_b128(src + i * (NW * 1024), dst + i * (NW * 1024));
     };
     auto load_v = [&](int t, int stage) {
         const unsigned char* src = vbase + (size_t)t * (KT * 2) + v_off;
         unsigned char* dst = v_stage + stage * V_TILE_BYTES + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_to_lds_b128(src + (size_t)i * 32 * cap * 2, dst + i * 4096);
+        for (int i = 0; i < LPT; ++i) load_to_lds_b128(src + (size_t)i * (8 * NW) * cap * 2, dst + i * (NW * 1024));
     };
     // Slots past kv_len may hold anything (NaN included) and 0 x NaN is not 0: blank them in the staged V^T tile.
     auto blank_v_tail = [&](int t, int stage) {
         const int n_valid = kv_len - t * KT;
         bf16* sv = reinterpret_cast<bf16*>(v_stage + stage * V_TILE_BYTES);
-        for (int idx = tid; idx < D * 8; idx += 256) {
+        for (int idx = tid; idx < D * 8; idx += 64 * NW) {
             const int row = idx >> 3, p = idx & 7;
             const int c = p ^ ((row >> 1) & 7);
             bf16x8 v = *reinterpret_cast<bf16x8*>(sv + row * KT + p * 8);
@@ -387,9 +389,21 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
 
 }  // namespace
 
+// Waves per workgroup: 4 (128 queries, two workgroups per compute unit) or 8 (256 queries, one workgroup per unit,
+// half the K/V traffic from the L2 per query).
+int attention_plan_waves(int B, int L, int H, int max_kv_len) {
+    const char* e = getenv("SDV2_ATTN_WAVES");       // tuning runs and tests; read at every call
+    if (e && (atoi(e) == 4 || atoi(e) == 8)) return atoi(e);
+    (void)max_kv_len;
+    // 256-query workgroups only where they still give at least half of the compute units a workgroup each
+    return ((L + 255) / 256) * H * B >= 128 ? 8 : 4;
+}
+
 int attention_plan_splits(int B, int L, int H, int max_kv_len) {
     const char* e = getenv("SDV2_ATTN_SPLITS");      // tuning runs and tests; read at every call
     const int forced = e ? atoi(e) : 0;
+    const int QT = 32 * attention_plan_waves(B, L, H, max_kv_len);
+    const int slots = QT == 128 ? 512 : 256;         // workgroups resident at once
     const int n_tiles = (max_kv_len + KT - 1) / KT;
     int splits = 1;
     if (forced > 0) {
@@ -399,8 +413,8 @@ int attention_plan_splits(int B, int L, int H, int max_kv_len) {
         // key tiles per split (the merge pass costs about as much as two tiles), and do not split at all
         // once every unit has a workgroup.
         const int wgs = ((L + QT - 1) / QT) * H * B;
-        if (wgs < 256) {
-            splits = 512 / wgs;
+        if (wgs < slots / 2) {
+            splits = slots / wgs;
             while (splits > 1 && n_tiles / splits < 6) --splits;
         }
     }
@@ -420,14 +434,22 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
     const size_t smem = (size_t)2 * K_TILE_BYTES + 2 * V_TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<4>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+    int max_kv = 0;
+    for (int b = 0; b < a.B; ++b) max_kv = a.kv_len[b] > max_kv ? a.kv_len[b] : max_kv;
+    const int nw = attention_plan_waves(a.B, a.L, a.H, max_kv);
+    const int QT = 32 * nw;
     dim3 grid((a.L + QT - 1) / QT, a.H, a.B * a.splits);
-    hipLaunchKernelGGL(attention_kernel, grid, dim3(256), smem, s, a, scale_log2e);
+    if (nw == 8) hipLaunchKernelGGL(attention_kernel<8>, grid, dim3(512), smem, s, a, scale_log2e);
+    else hipLaunchKernelGGL(attention_kernel<4>, grid, dim3(256), smem, s, a, scale_log2e);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (a.splits > 1) {

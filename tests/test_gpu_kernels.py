@@ -157,8 +157,9 @@ ATTN_CASES = [
 ]
 
 
+@pytest.mark.parametrize("waves", [0, 4, 8])        # 0: the planner's choice; 4 / 8 waves (128 / 256 queries) per workgroup
 @pytest.mark.parametrize("B,L,H,kv_lens,splits", ATTN_CASES)
-def test_attention_matches_oracle(B, L, H, kv_lens, splits):
+def test_attention_matches_oracle(B, L, H, kv_lens, splits, waves):
     D = 128
     Cw = H * D
     q = bf16_randn((B, L, Cw), 10)
@@ -176,12 +177,15 @@ def test_attention_matches_oracle(B, L, H, kv_lens, splits):
     o = torch.full((B, L, Cw), float("nan"), dtype=torch.bfloat16, device=DEV)
     if splits:
         os.environ["SDV2_ATTN_SPLITS"] = str(splits)
+    if waves:
+        os.environ["SDV2_ATTN_WAVES"] = str(waves)
     try:
         ws = torch.empty(max(binding.attention_workspace_bytes(B, L, Cw, max(kv_lens)), 256), dtype=torch.uint8, device=DEV)
         binding.attention_bf16(q.to(DEV), ks, vts, kv_lens, caps, o, H, ws)
         torch.cuda.synchronize()
     finally:
         os.environ.pop("SDV2_ATTN_SPLITS", None)
+        os.environ.pop("SDV2_ATTN_WAVES", None)
     got = f64(o)
     assert np.isfinite(got).all()
     for b in range(B):
