@@ -511,7 +511,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_dma_kernel(GemmArgs g, i
 // even stream three tiles ahead instead of a burst after the barrier that blocks the issuing waves) and reads
 // the next k step's fragments between the MFMAs of the current one.
 template <int WM, int WN, int TM, int TN>
-__global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+__global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m,
+                                                           int splitk) {
     static_assert(WM * WN == 8, "eight waves");
     constexpr int NW = 8, BK = 32, NS = 4;
     constexpr int BM = 32 * TM * WM;
@@ -532,8 +533,10 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles
 
     const int nwg = gridDim.x;
     const int logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
-    const int t = logical;
-    if (t >= tiles_m * tiles_n) return;
+    const int tiles = tiles_m * tiles_n;
+    if (logical >= tiles * splitk) return;
+    const int ks = logical / tiles;                              // which part of k (0 when k is not split)
+    const int t = logical - ks * tiles;
     const int group_size = group_m * tiles_n;
     const int grp = t / group_size;
     const int first_m = grp * group_m;
@@ -543,7 +546,14 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles
     const int tile_n = in_grp / gm;
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
-    const int nk = g.K / BK;
+    const int nk_all = g.K / BK;
+    const int kt0 = (int)((long long)ks * nk_all / splitk);
+    const int nk = (int)((long long)(ks + 1) * nk_all / splitk) - kt0;
+    if (splitk > 1) {                                            // this part's fp32 partial sums, plain stores
+        g.out = g.splitk_partials + (size_t)ks * g.M * g.N;
+        g.epilogue = kEpiPartial;
+        g.bias = nullptr;
+    }
 
     uint32_t off[LPW];
     {
@@ -556,8 +566,8 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles
             off[i] = (uint32_t)row * (uint32_t)g.K * 2u + (uint32_t)c * 16u;
         }
     }
-    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.a);
-    const unsigned char* w_base = reinterpret_cast<const unsigned char*>(g.w);
+    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.a) + (size_t)kt0 * (BK * 2);
+    const unsigned char* w_base = reinterpret_cast<const unsigned char*>(g.w) + (size_t)kt0 * (BK * 2);
     // load i of tile kt (clamped: past the end the last tile is fetched again into a stage nobody reads) into
     // the stage of iteration index st
     auto issue_load = [&](auto ic, int kt, int st) {
@@ -651,13 +661,13 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles
 }
 
 template <int WM, int WN, int TM, int TN>
-hipError_t launch_ring(const GemmArgs& g, hipStream_t s) {
+hipError_t launch_ring(const GemmArgs& g, int splitk, hipStream_t s) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t smem = (size_t)4 * (BM + BN) * 32 * sizeof(bf16);
     static_assert(smem <= 160 * 1024 && smem >= (size_t)8 * EPI_WAVE_FLOATS * sizeof(float), "LDS");
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.N + BN - 1) / BN;
-    const int grid = (tiles_m * tiles_n + 7) / 8 * 8;
+    const int grid = (tiles_m * tiles_n * splitk + 7) / 8 * 8;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<WM, WN, TM, TN>),
@@ -667,7 +677,7 @@ hipError_t launch_ring(const GemmArgs& g, hipStream_t s) {
     }
     // groups of four tile rows: an XCD's 32 concurrent tiles then cover 4 x 8 tiles, the shape with the fewest
     // distinct operand rows per k step
-    hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 4);
+    hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 4, splitk);
     return hipGetLastError();
 }
 
@@ -710,7 +720,7 @@ const TunedShape kTuned[] = {
     // (QKV runs with three register sets and FFN-1 with two: equally fast, and each then has a kernel name of its own
     // in a profile)
     {1024, 4608, 1536, {1, 5, 3}},  {1024, 1536, 1536, {1, 2, 2}}, {1024, 8960, 1536, {1, 5, 2}},   {1024, 1536, 8960, {1, 6, 2, 0, 4}},
-    {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {1, 5, 2}},
+    {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {0, 0, 0, 5, 3}},      // FFN-2 14B: ring, 256 x 256 tiles, three k parts
 };
 
 // Otherwise: when 256 x 256 tiles fill at least 80 % of the compute units in every round, the direct-load
@@ -790,14 +800,14 @@ hipError_t launch_tn(const GemmArgs& g, int tn, int splitk, hipStream_t s) {
 
 // Configurations of the direct-load kernel: (waves on M, waves on N, TM, TN, LDS stages).
 constexpr int kDmaConfigs = 6;
-hipError_t launch_dma_config(const GemmArgs& g, int id, hipStream_t s) {
+hipError_t launch_dma_config(const GemmArgs& g, int id, int splitk, hipStream_t s) {
     switch (id) {
         case 1: return launch_dma<4, 2, 2, 4, 2>(g, s);      // 256 x 256, wave tile 64 x 128
         case 2: return launch_dma<2, 4, 4, 2, 2>(g, s);      // 256 x 256, wave tile 128 x 64
         case 3: return launch_dma<2, 4, 2, 2, 3>(g, s);      // 128 x 256
         case 4: return launch_dma<4, 2, 2, 2, 3>(g, s);      // 256 x 128
-        case 5: return launch_ring<4, 2, 2, 4>(g, s);        // 256 x 256, ring of four k32 stages
-        case 6: return launch_ring<2, 4, 4, 2>(g, s);
+        case 5: return launch_ring<4, 2, 2, 4>(g, splitk, s);        // 256 x 256, ring of four k32 stages
+        case 6: return launch_ring<2, 4, 4, 2>(g, splitk, s);
     }
     return hipErrorInvalidValue;
 }
@@ -805,12 +815,14 @@ hipError_t launch_dma_config(const GemmArgs& g, int id, hipStream_t s) {
 }  // namespace
 
 // Environment override for tuning runs and tests, read at every call: SDV2_GEMM_TILE="tm,tn[,pf[,splitk]]" picks a
-// tile of the register-staged kernel, "d<id>" a configuration of the direct-load kernel.
+// tile of the register-staged kernel, "d<id>[,splitk]" a configuration of the direct-load kernel (only its ring form,
+// d5 and d6, splits k).
 static bool tile_override(TilePlan* p) {
     const char* e = getenv("SDV2_GEMM_TILE");
     int a, b, d = 2;
-    if (e && sscanf(e, "d%d", &a) == 1 && a >= 1 && a <= kDmaConfigs) {
-        *p = TilePlan{0, 0, 0, a};
+    int dk = 1;
+    if (e && sscanf(e, "d%d,%d", &a, &dk) >= 1 && a >= 1 && a <= kDmaConfigs && dk >= 1 && dk <= 16) {
+        *p = TilePlan{0, 0, 0, a, (a == 5 || a == 6) ? dk : 1};      // only the ring form splits k
         return true;
     }
     int k = 1;
@@ -854,7 +866,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
 
 // Parts of k the plan can really use for this problem and scratch (1: no split).
 static int usable_splitk(const GemmArgs& g, const TilePlan& p) {
-    if (p.dma || p.splitk <= 1 || g.splitk_partials == nullptr) return 1;
+    if ((p.dma && p.dma != 5 && p.dma != 6) || p.splitk <= 1 || g.splitk_partials == nullptr) return 1;
     int splitk = p.splitk;
     if (splitk > g.K / 128) splitk = g.K / 128;                 // at least two k tiles per part
     if (splitk < 2 || (size_t)splitk * g.M * g.N > g.splitk_floats) return 1;
@@ -864,10 +876,10 @@ static int usable_splitk(const GemmArgs& g, const TilePlan& p) {
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue);
     tile_override(&p);
-    if (p.dma) return launch_dma_config(g, p.dma, s);
     const int splitk = usable_splitk(g, p);
     hipError_t e;
-    if (p.pf == 3) e = p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
+    if (p.dma) e = launch_dma_config(g, p.dma, splitk, s);
+    else if (p.pf == 3) e = p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
     else e = p.tm == 1 ? launch_tn<1, 2>(g, p.tn, splitk, s) : launch_tn<2, 2>(g, p.tn, splitk, s);
     if (e != hipSuccess || splitk == 1) return e;
     const size_t n = (size_t)g.M * (g.N >> 2);
@@ -878,7 +890,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
 size_t gemm_splitk_floats(int M, int N, int K, int epilogue) {
     TilePlan p = plan_tiles(M, N, K, epilogue);
     tile_override(&p);
-    if (p.dma || p.splitk <= 1) return 0;
+    if ((p.dma && p.dma != 5 && p.dma != 6) || p.splitk <= 1) return 0;
     return (size_t)p.splitk * M * N;
 }
 

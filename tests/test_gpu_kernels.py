@@ -60,6 +60,8 @@ GEMM_CASES = [
     (300, 640, 192, 2, "d6"),              # ring variant, N not a multiple of the tile, 6 k tiles
     (256, 256, 64, 3, "d6"),               # two k tiles: fewer than the ring holds
     (130, 256, 32 * 2, 0, "d5"),           # K = 64
+    (520, 768, 1024, 2, "d6,3"),           # ring with three k parts (fp32 partial sums + reduce), gated residual
+    (1000, 512, 640, 1, "d5,2"),           # ring, two k parts, GELU in the reduce pass, ragged M
     (300, 512, 1024, 2, "1,4,2,2"),        # k split in two parts + reduce kernel, gated residual, ragged M
     (260, 256, 2048, 3, "2,8,2,4"),        # four parts, residual
     (1024, 1536, 1536, 1, "1,5,2,3"),      # three parts, GELU in the reduce kernel, ragged N tile
