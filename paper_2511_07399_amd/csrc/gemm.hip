@@ -721,6 +721,9 @@ const TunedShape kTuned[] = {
     // in a profile)
     {1024, 4608, 1536, {1, 5, 3}},  {1024, 1536, 1536, {1, 2, 2}}, {1024, 8960, 1536, {1, 5, 2}},   {1024, 1536, 8960, {1, 6, 2, 0, 4}},
     {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {0, 0, 0, 5, 3}},      // FFN-2 14B: ring, 256 x 256 tiles, three k parts
+    // the 1.3B block with 2 or 4 streams per call, where the rule below is more than 4 % off the sweep's best
+    {2048, 1536, 8960, {1, 6, 2, 0, 2}}, {4096, 8960, 1536, {1, 5, 2}}, {4096, 1536, 8960, {1, 6, 2}},
+    {4096, 1536, 1536, {1, 6, 2}},
 };
 
 // Otherwise: when 256 x 256 tiles fill at least 80 % of the compute units in every round, the direct-load
