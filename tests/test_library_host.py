@@ -120,3 +120,14 @@ def test_slo_pick_batch_matches_the_oracle_on_random_tables():
             assert False, "accepted a bad argument"
         except binding.Sdv2Error as e:
             assert e.code == binding.INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU only: bench.py --gpus N with N > 1 says so and exits without touching a GPU."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
