@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--workload", default="wan1.3b-step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary 14B-shaped measurement")
+    ap.add_argument("--dist-chunks", type=int, default=60,
+                    help="steady-state chunks in the latency-distribution pass (skipped with --no-also)")
     ap.add_argument("--batch-sweep", default="",
                     help="comma-separated batch sizes (1..8): instead of the usual line, measure the step latency "
                          "L(T, B) of the workload with B streams per call and print the table with the batch size "
@@ -65,7 +67,7 @@ def main():
     if args.batch_sweep:
         print(json.dumps(batch_sweep(args.workload, [int(b) for b in args.batch_sweep.split(",")], args.steps, args.warmup)))
         return
-    m = measure(args.workload, args.steps, args.warmup, args.copy_calibration)
+    m = measure(args.workload, args.steps, args.warmup, args.copy_calibration, 0 if args.no_also else args.dist_chunks)
     ms_per_step, wall_ms, kernels, roofline = m["ms_per_step"], m["wall_ms"], m["kernels"], m["roofline"]
     step_flops, gemm_tflops, attn_tflops, l_kv = m["step_flops"], m["gemm_tflops"], m["attn_tflops"], m["l_kv"]
     B, L, Cw = wl.B, wl.L, wl.C
@@ -106,12 +108,12 @@ def main():
         "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
         "step_frac_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / cm.MI355X_BF16_FLOPS, 4),
         "gemm_tflops": round(gemm_tflops, 1), "attn_tflops": round(attn_tflops, 1),
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "also": also,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "latency": m["latency"], "also": also,
     }
     print(json.dumps(out))
 
 
-def measure(workload, steps, warmup, copy_calibration):
+def measure(workload, steps, warmup, copy_calibration, n_dist=0):
     """Steady-state timing of sdv2_denoise_step on one workload: the headline pass and the per-launch pass."""
     import numpy as np
     import torch
@@ -218,12 +220,57 @@ def measure(workload, steps, warmup, copy_calibration):
         "flops_per_launch": flops[dom], "traffic": load_traffic(wl.name, "FFN-1 gemm"),
     }
     step_flops = wl.N * cm.block_flops(rows, Cw, wl.F, l_kv, wl.L_t)
+    latency = None
+    if n_dist:
+        # bound the pass to about ten seconds of GPU time
+        per_chunk_ms = ms_per_step * sum(set((1,) + tuple(wl.steps)))
+        latency = latency_distribution(gpu, wl, xs, min(n_dist, max(8, int(10000.0 / per_chunk_ms))))
     gpu.close()
     del gpu, xs, prepared
     torch.cuda.empty_cache()
     return {"ms_per_step": ms_per_step, "wall_ms": wall_ms, "kernels": kernels, "roofline": roofline,
-            "step_flops": step_flops, "gemm_tflops": gemm_tflops, "attn_tflops": attn_tflops, "l_kv": l_kv}
+            "step_flops": step_flops, "gemm_tflops": gemm_tflops, "attn_tflops": attn_tflops, "l_kv": l_kv,
+            "latency": latency}
 
+
+
+def latency_distribution(gpu, wl, xs, n_chunks):
+    """Per-chunk latency of a stream started from an empty cache: every denoise step is bracketed by events on the
+    launch stream (no synchronisation until the end).  Reports the warm-up chunks (the cache is filling, fewer keys)
+    one by one and the distribution over the steady-state chunks, for 1 denoising step per chunk and for the other
+    step counts the workload names (all steps of a chunk summed; steps after the first rewrite the chunk's K/V)."""
+    import numpy as np
+    import torch
+    from paper_2511_07399_amd import binding, workloads as wk
+    stream = torch.cuda.current_stream()
+    B, frames = wl.B, wl.frames_per_chunk
+    fill = (wl.sink_frames + wl.window_frames + frames - 1) // frames
+    out = {}
+    for n_steps in sorted(set((1,) + tuple(wl.steps))):
+        for s_id in range(B):
+            binding.kv_cache_reset(gpu.cache, s_id)
+        total = fill + n_chunks
+        inputs = [xs[c % len(xs)].clone() for c in range(min(total, 16))]
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_steps + 1)] for _ in range(total)]
+        torch.cuda.synchronize()
+        for c in range(total):
+            x = inputs[c % len(inputs)]
+            evs[c][0].record(stream)
+            for st in range(n_steps):
+                descs = [(s_id, c * frames, frames, 1 if st == 0 else 0) for s_id in range(B)]
+                ts = [wk.timestep(wl, c, st, s_id) for s_id in range(B)]
+                gpu.denoise(x, descs, timesteps=ts)
+                evs[c][st + 1].record(stream)
+        torch.cuda.synchronize()
+        per_chunk = np.array([evs[c][0].elapsed_time(evs[c][n_steps]) for c in range(total)])
+        steady = per_chunk[fill:]
+        q = lambda p: round(float(np.percentile(steady, p)), 4)
+        out["%d step(s) per chunk" % n_steps] = {
+            "warmup_chunk_ms": [round(float(v), 4) for v in per_chunk[:fill]],
+            "steady_chunk_ms": {"n": int(steady.size), "median": q(50), "p10": q(10), "p90": q(90), "p99": q(99),
+                                "mean": round(float(steady.mean()), 4)},
+        }
+    return out
 
 
 def batch_sweep(workload, sizes, steps, warmup):
