@@ -159,7 +159,8 @@ def dit_block_forward(x, e0, w, cache, text_k, text_v, n_heads, tokens_per_frame
     k_res, v_res = cache.gather()                      # every resident token, this chunk included
     n_res = k_res.shape[0]
     attn = attention_dense(q, k_res.reshape(n_res, H, D), v_res.reshape(n_res, H, D)).reshape(L, C)
-    x = x + gate1 * linear(attn, f(w["W_o"]), f(w["b_o"]))
+    upd_self = gate1 * linear(attn, f(w["W_o"]), f(w["b_o"]))
+    x = x + upd_self
 
     # text cross-attention branch (no gate, no RoPE)
     hc = layer_norm(x, f(w["ln3_gamma"]), f(w["ln3_beta"]))
@@ -167,15 +168,19 @@ def dit_block_forward(x, e0, w, cache, text_k, text_v, n_heads, tokens_per_frame
     L_t = text_k.shape[0]
     cross = attention_dense(qc.reshape(L, H, D), f(text_k).reshape(L_t, H, D),
                             f(text_v).reshape(L_t, H, D)).reshape(L, C)
-    x = x + linear(cross, f(w["W_co"]), f(w["b_co"]))
+    upd_cross = linear(cross, f(w["W_co"]), f(w["b_co"]))
+    x = x + upd_cross
 
     # feed-forward branch
     h2 = layer_norm(x) * (1.0 + scale2) + shift2
     u = gelu_tanh(linear(h2, f(w["W_1"]), f(w["b_1"])))
-    x = x + gate2 * linear(u, f(w["W_2"]), f(w["b_2"]))
+    upd_ffn = gate2 * linear(u, f(w["W_2"]), f(w["b_2"]))
+    x = x + upd_ffn
 
     if debug is not None:
-        debug.update(h=h, q=q.reshape(L, C), k=k, v=v, attn=attn, qc=qc, cross=cross, u=u)
+        # what each of the three branches added to x (tests check that none of them hides below the tolerance)
+        debug.update(h=h, q=q.reshape(L, C), k=k, v=v, attn=attn, qc=qc, cross=cross, u=u,
+                     upd_self=upd_self, upd_cross=upd_cross, upd_ffn=upd_ffn)
     return x
 
 

@@ -14,7 +14,11 @@ class DeviceModel:
     """Device tensors, C structs, cache, text K/V and workspace of one workload on one GPU."""
 
     def __init__(self, wl, base_seed=0, device="cuda:0", n_layers=None, n_streams=None, weight_device="cpu",
-                 sink_tokens=None, window_tokens=None):
+                 sink_tokens=None, window_tokens=None, edit=None):
+        """weight_device: where the seeded generators run ("cpu" values are the ones a host-side checker can
+        redraw; a CUDA generator draws other values from the same seed), or a callable layer -> device.
+        edit: optional callable (tensors, layer) applied to each layer's freshly drawn tensors, in place, before
+        they are uploaded (tests use it to rescale gates or to switch a branch off)."""
         binding.load_library()
         self.wl = wl
         self.device = torch.device(device)
@@ -26,13 +30,16 @@ class DeviceModel:
         self.layers = []
         self.bw_array = (binding.BlockWeights * self.N)()
         for layer in range(self.N):
-            w = wk.block_weights(wl, layer, base_seed, device=weight_device)
+            wdev = weight_device(layer) if callable(weight_device) else weight_device
+            w = wk.block_weights(wl, layer, base_seed, device=wdev)
+            if edit is not None:
+                edit(w, layer)
             t = {k: v.to(self.device) for k, v in w.items()}
             t["W_qkv"] = torch.cat([t.pop("W_q"), t.pop("W_k"), t.pop("W_v")], 0).contiguous()
             t["b_qkv"] = torch.cat([t.pop("b_q"), t.pop("b_k"), t.pop("b_v")], 0).contiguous()
             self.layers.append(t)
             self.bw_array[layer] = binding.block_weights(t)
-        mw = wk.model_weights(wl, base_seed, device=weight_device)
+        mw = wk.model_weights(wl, base_seed, device="cpu" if callable(weight_device) else weight_device)
         self.mw_t = {k: v.to(self.device) for k, v in mw.items()}
         self.mw = binding.model_weights(self.mw_t, self.bw_array)
         # cache: poisoned with 0xFF bytes (bf16 NaN, id -1) so that a read of an unfilled slot shows up

@@ -18,26 +18,79 @@ def max_rel_err(got, want):
     return float(np.abs(got - want).max() / max(np.abs(want).max(), 1e-30))
 
 
+# (gate 1, gate 2, scale of the cross-attention output projection) that put each branch's largest contribution to
+# x near 1 for a model shape (C, F, tokens per frame); found by running the oracle once per shape on the seeded
+# weights (the self-attention output shrinks with the number of keys, the FFN output grows with C and F).
+_BRANCH_SCALES = {
+    (512, 2048, 128): (8.0, 1.0, 4.0),
+    (1536, 8960, 1024): (8.0, 0.25, 4.0),
+    (5120, 13824, 1024): (3.0, 0.1, 1.0),
+    (5120, 13824, 1560): (6.0, 0.1, 1.0),
+}
+
+
+def visible_branches(wl):
+    """Weight edit (applied to the seeded tensors of BOTH sides) that makes every branch of the block show at its
+    output.  With the seeded N(0, 0.02^2) modulation table the gates are about 0.03 and the self-attention branch
+    adds about 0.5 % of max |x| to the block output, four times below the 2e-2 bar: a block whose attention over the
+    cache returned nothing would pass.  The edit moves gate 1 and gate 2 by a constant of alternating sign over the
+    channels and scales the ungated cross-attention output projection (all bf16-exact), so that each branch's largest
+    contribution is near 1, about ten times the absolute tolerance at max |x| of 5 to 6."""
+    g1, g2, sc = _BRANCH_SCALES.get((wl.C, wl.F, wl.P), (8.0, 0.25, 4.0))
+
+    def edit(w, layer=0):
+        C = w["mod_table"].shape[1]
+        sign = torch.ones(C, dtype=w["mod_table"].dtype, device=w["mod_table"].device)
+        sign[1::2] = -1.0
+        w["mod_table"][2] += g1 * sign
+        w["mod_table"][5] += g2 * sign
+        w["W_co"] *= sc
+        w["b_co"] *= sc
+    return edit
+
+
+def self_attention_alone(w, layer=0):
+    """Weight edit that leaves the self-attention branch as the only thing the block adds to x: no cross-attention
+    output (W_co = b_co = 0), gate 2 = 0 (with a zero e0 row), no output bias, gate 1 of magnitude 1."""
+    C = w["mod_table"].shape[1]
+    sign = torch.ones(C, dtype=w["mod_table"].dtype, device=w["mod_table"].device)
+    sign[1::2] = -1.0
+    w["mod_table"][2] = sign
+    w["mod_table"][5] = 0.0
+    w["W_co"] *= 0.0
+    w["b_co"] *= 0.0
+    w["b_o"] *= 0.0
+
+
+def branch_floor(dbg):
+    """Smallest of the three branches' largest contributions to x in one oracle block call."""
+    return min(float(np.abs(dbg[k]).max()) for k in ("upd_self", "upd_cross", "upd_ffn"))
+
+
 class OracleRunner:
     def __init__(self, wl, base_seed=0, n_layers=None, n_streams=None, sink_tokens=None, window_tokens=None,
-                 dtype=np.float64):
+                 dtype=np.float64, edit=None, layer_ids=None):
+        """layer_ids: the layers this runner holds (default: 0 .. n_layers-1); edit: as in DeviceModel."""
         self.wl = wl
         self.dtype = dtype
         self.N = wl.N if n_layers is None else n_layers
+        self.layer_ids = list(range(self.N)) if layer_ids is None else list(layer_ids)
         self.n_streams = wl.B if n_streams is None else n_streams
         S = wl.S if sink_tokens is None else sink_tokens
         W = wl.W if window_tokens is None else window_tokens
-        self.layers = [wk.to_numpy(wk.block_weights(wl, layer, base_seed)) for layer in range(self.N)]
-        self.mw = wk.to_numpy(wk.model_weights(wl, base_seed))
-        self.caches = [[oracle.RollingKVCache(S, W, wl.P, wl.C, dtype=dtype) for _ in range(self.n_streams)]
-                       for _ in range(self.N)]
-        self.text = []
-        for layer in range(self.N):
+        self.layers, self.caches, self.text = {}, {}, {}
+        for layer in self.layer_ids:
+            w = wk.block_weights(wl, layer, base_seed)
+            if edit is not None:
+                edit(w, layer)
+            self.layers[layer] = wk.to_numpy(w)
+            self.caches[layer] = [oracle.RollingKVCache(S, W, wl.P, wl.C, dtype=dtype) for _ in range(self.n_streams)]
             per_stream = []
             for s in range(self.n_streams):
                 ctx = wk.text_context(wl, s, base_seed).double().numpy()
                 per_stream.append(oracle.text_kv_prepare(ctx, self.layers[layer], dtype=dtype))
-            self.text.append(per_stream)
+            self.text[layer] = per_stream
+        self.mw = wk.to_numpy(wk.model_weights(wl, base_seed))
 
     def conditioning(self, timestep=None, tvec=None):
         return oracle.conditioning(self.mw, t=timestep, tvec=tvec, dtype=self.dtype)
@@ -49,15 +102,16 @@ class OracleRunner:
                                         self.wl.P, self.wl.grid_w, frame_pos0, advance=bool(advance),
                                         dtype=self.dtype, debug=debug)
 
-    def denoise(self, x, desc, timestep=None, tvec=None):
+    def denoise(self, x, desc, timestep=None, tvec=None, debug=None):
+        """debug: optional dict that receives the intermediates of the LAST layer."""
         e0 = self.conditioning(timestep, tvec)
-        for layer in range(self.N):
-            x = self.block(layer, x, e0, desc)
+        for layer in self.layer_ids:
+            x = self.block(layer, x, e0, desc, debug=debug if layer == self.layer_ids[-1] else None)
         return x
 
 
 def run_stream_both(wl, n_chunks, steps=1, device="cuda:0", base_seed=0, use_timesteps=None, n_layers=None,
-                    check_cache=True, cache_chunks=None):
+                    check_cache=True, cache_chunks=None, edit=None):
     """Single stream, ``n_chunks`` chunks of ``steps`` denoising steps, on both sides.
 
     Returns per-chunk output errors, and whether host state, host slot map and device id map equal the
@@ -67,8 +121,8 @@ def run_stream_both(wl, n_chunks, steps=1, device="cuda:0", base_seed=0, use_tim
     N = wl.N if n_layers is None else n_layers
     if use_timesteps is None:
         use_timesteps = wl.name != "tiny"
-    gpu = GpuRunner(wl, base_seed, device, n_layers=N, n_streams=1)
-    ora = OracleRunner(wl, base_seed, n_layers=N, n_streams=1)
+    gpu = GpuRunner(wl, base_seed, device, n_layers=N, n_streams=1, edit=edit)
+    ora = OracleRunner(wl, base_seed, n_layers=N, n_streams=1, edit=edit)
     res = {"x_err": [], "k_err": [], "v_err": [], "state_equal": True, "slot_map_equal": True, "ids_equal": True}
     for chunk in range(n_chunks):
         x_host = wk.chunk_input(wl, chunk, 0, base_seed)

@@ -13,11 +13,58 @@ import torch
 import oracle
 
 from paper_2511_07399_amd import binding, workloads as wk
-from parity_util import GpuRunner, OracleRunner, max_rel_err, run_stream_both
+from parity_util import (GpuRunner, OracleRunner, branch_floor, max_rel_err, run_stream_both, self_attention_alone,
+                         visible_branches)
 
 pytestmark = pytest.mark.gpu
 TOL_X = 2e-2
 TOL_KV = 1e-2
+
+
+def caller_e0(wl, chunk, stream=0, zero_rows=()):
+    """A caller-made modulation [6, C] ~ N(0, 0.02^2), bf16-exact, seeded; rows in `zero_rows` are zero."""
+    g = torch.Generator().manual_seed(77_000 + 131 * chunk + stream)
+    e0 = (torch.randn(6, wl.C, generator=g) * 0.02).to(torch.bfloat16).to(torch.float32)
+    for r in zero_rows:
+        e0[r] = 0.0
+    return e0
+
+
+def run_blocks_both(wl, n_chunks, edit, zero_rows=(), compare="output", cache_chunks=(), layer=0):
+    """One stream through ONE block (sdv2_dit_block_forward with a caller-made e0) on both sides.  compare =
+    "output": error of x_out relative to max |x_out|, and every branch's largest contribution (from the oracle) must
+    exceed 5 x the absolute tolerance; "update": error of x_out - x_in relative to max |x_out - x_in|."""
+    gpu = GpuRunner(wl, n_layers=1, n_streams=1, edit=edit)
+    ora = OracleRunner(wl, n_layers=1, n_streams=1, edit=edit)
+    errs = []
+    for chunk in range(n_chunks):
+        x = wk.chunk_input(wl, chunk)
+        e0 = caller_e0(wl, chunk, 0, zero_rows)
+        desc = (0, chunk * wl.frames_per_chunk, wl.frames_per_chunk, 1)
+        xg = x.to(gpu.device).reshape(1, wl.L, wl.C).contiguous()
+        gpu.block(layer, xg, e0.to(gpu.device).reshape(1, 6, wl.C).contiguous(), [desc])
+        dbg = {}
+        xo = ora.block(layer, x.double().numpy(), e0.double().numpy(), desc, debug=dbg)
+        got = xg[0].cpu().double().numpy()
+        if compare == "output":
+            floor = branch_floor(dbg)
+            assert floor >= 5 * TOL_X * np.abs(xo).max(), ("a branch hides below the tolerance", chunk, floor)
+            errs.append(max_rel_err(got, xo))
+        else:
+            upd = xo - x.double().numpy()
+            assert np.abs(upd - dbg["upd_self"]).max() <= 1e-9 * np.abs(upd).max()      # nothing else was added
+            errs.append(max_rel_err(got - x.double().numpy(), upd))
+        oc = ora.caches[layer][0]
+        assert gpu.state(layer, 0) == oc.state(), chunk
+        assert np.array_equal(gpu.slot_map(layer, 0), oc.slot_map()), chunk
+        if chunk in cache_chunks:
+            K, V, ids = gpu.cache_logical(layer, 0)
+            live = oc.slot_map() >= 0
+            assert np.array_equal(ids[live], oc.slot_map()[live])
+            ko, vo = oc.slot_contents()
+            assert max_rel_err(K[live], ko[live]) <= TOL_KV and max_rel_err(V[live], vo[live]) <= TOL_KV
+    gpu.close()
+    return errs
 
 
 def check(res):
@@ -57,6 +104,22 @@ def test_tiny_two_denoising_steps_per_chunk():
     """Step 2 of a chunk rewrites the chunk's K/V in place and moves nothing."""
     res = run_stream_both(wk.WORKLOADS["tiny"], n_chunks=5, steps=2)
     check(res)
+
+
+def test_tiny_four_denoising_steps_per_chunk():
+    """advance = 0 three times in a row after every append (four denoising steps per chunk), with gates of
+    order one so that the rewritten keys and values show at the output."""
+    wl = wk.WORKLOADS["tiny"]
+    res = run_stream_both(wl, n_chunks=5, steps=4, edit=visible_branches(wl))
+    check(res)
+
+
+def test_tiny_visible_branches_and_self_attention_alone():
+    wl = wk.WORKLOADS["tiny"]
+    errs = run_blocks_both(wl, 6, visible_branches(wl), cache_chunks=(5,))
+    assert max(errs) <= TOL_X, errs
+    errs = run_blocks_both(wl, 6, self_attention_alone, zero_rows=(2, 5), compare="update")
+    assert max(errs) <= TOL_X, errs
 
 
 def test_ragged_three_frame_chunks_with_mid_append_wrap():
@@ -128,29 +191,137 @@ def test_wan13b_block_long_stream():
     assert len(res["x_err"]) == 64 and len(res["k_err"]) == 3
 
 
+def test_wan13b_block_visible_branches_through_eviction():
+    """1.3B-shaped block at full size with gates of order one (every branch adds about ten times the absolute
+    tolerance, asserted from the oracle's own branch outputs): warm-up chunks 0-2, first evictions 3 and 4."""
+    wl = wk.WORKLOADS["wan1.3b-block"]
+    errs = run_blocks_both(wl, 5, visible_branches(wl), cache_chunks=(4,))
+    print("x_err", errs, flush=True)
+    assert max(errs) <= TOL_X, errs
+
+
+def test_wan13b_block_self_attention_alone_through_eviction():
+    """The block's update IS the self-attention branch (no cross-attention output, gate 2 = 0): what the chunk's
+    queries read from [sink | window | chunk] is compared relative to the update itself, through the first
+    evictions.  A stale frame, a short key range or a wrong cache pointer moves this by tens of percent."""
+    errs = run_blocks_both(wk.WORKLOADS["wan1.3b-block"], 5, self_attention_alone, zero_rows=(2, 5), compare="update")
+    print("update err", errs, flush=True)
+    assert max(errs) <= TOL_X, errs
+
+
 def test_wan13b_block_first_chunks():
     """1.3B-shaped block at full size: warm-up chunks 0-2 and the first evictions (3, 4)."""
     res = run_stream_both(wk.WORKLOADS["wan1.3b-block"], n_chunks=5, check_cache=True)
     check(res)
 
 
-@pytest.mark.timeout(600)
+@pytest.mark.timeout(900)
 def test_wan13b_step_full_depth():
-    """30 blocks in sequence with timestep conditioning: two chunks with one denoising step, one chunk with two.
-    (The oracle needs about half a second per block; evictions at full size are covered one block deep above.)"""
+    """30 blocks in sequence with timestep conditioning.  Chunks 0-3 with one denoising step (the first eviction
+    happens at depth, in all 30 per-layer caches; the cached K/V of every layer are compared after chunk 3) and gates
+    of order one in seven of the layers, so that what their attention reads from the cache reaches the output; then one chunk with four denoising steps (advance = 0 three
+    times at depth) on the plain seeded weights."""
     wl = wk.WORKLOADS["wan1.3b-step"]
-    res = run_stream_both(wl, n_chunks=2, steps=1, check_cache=False)
+    vis = visible_branches(wl)
+    # gates of order one in every fifth block and in the last: in all 30 the hidden state would grow a hundredfold
+    edit = lambda w, layer: vis(w, layer) if layer % 5 == 0 or layer == wl.N - 1 else None
+    res = run_stream_both(wl, n_chunks=4, steps=1, check_cache=True, cache_chunks=(3,), edit=edit)
+    print("1 step, chunks 0-3:", res["x_err"], flush=True)
     check(res)
-    res = run_stream_both(wl, n_chunks=1, steps=2, check_cache=False)
+    res = run_stream_both(wl, n_chunks=1, steps=4, check_cache=False)
+    print("4 steps, chunk 0:", res["x_err"], flush=True)
     check(res)
 
 
 @pytest.mark.timeout(600)
 def test_wan14b_block_full_size():
-    """One 14B-shaped block (C 5120, 40 heads, FFN 13824) through warm-up and first eviction."""
+    """One 14B-shaped block (C 5120, 40 heads, FFN 13824) through warm-up and first eviction, gates of order one."""
     wl = wk.WORKLOADS["wan14b-step"]
-    res = run_stream_both(wl, n_chunks=4, n_layers=1, check_cache=False)
-    check(res)
+    errs = run_blocks_both(wl, 4, visible_branches(wl))
+    print("x_err", errs, flush=True)
+    assert max(errs) <= TOL_X, errs
+
+
+@pytest.mark.timeout(900)
+def test_wan14b_step_layers_0_19_39_fed_the_gpu_layer_input():
+    """The 40-block 14B-shaped model on chunks 0-3 (warm-up and first eviction in every layer's cache): the library
+    runs all 40 blocks; the oracle runs ONE block (0, then 19, then 39, a pass over the four chunks each) on the
+    hidden state the library fed to that block, with its own cache history for the block, and is compared on what
+    the block ADDS to x, relative to the largest addition.  The compared block has gates of order one (switched on
+    in place in its device tensors for its pass: with all of them on, x_in at depth is no longer like the input the
+    gate scales were found for); the other 37 layers draw their weights on the device."""
+    wl = wk.WORKLOADS["wan14b-step"]
+    picked = (0, 19, 39)
+    dev = "cuda:0"
+    gpu = GpuRunner(wl, n_streams=1, weight_device=lambda layer: "cpu" if layer in picked else dev)
+    vis = visible_branches(wl)
+    for target in picked:
+        plain = {k: gpu.layers[target][k].clone() for k in ("mod_table", "W_co", "b_co")}
+        vis(gpu.layers[target], target)                       # in place: the C structs keep pointing at these tensors
+        ora = OracleRunner(wl, n_streams=1, layer_ids=(target,), edit=vis)
+        binding.kv_cache_reset(gpu.cache, 0)
+        for chunk in range(4):
+            t = wk.timestep(wl, chunk)
+            e0g = gpu.conditioning(1, timesteps=[t])
+            e0o = ora.conditioning(timestep=t)
+            assert max_rel_err(e0g[0].cpu().numpy(), e0o) <= 1e-3
+            xg = wk.chunk_input(wl, chunk).to(dev).reshape(1, wl.L, wl.C).contiguous()
+            desc = (0, chunk, 1, 1)
+            for layer in range(wl.N):
+                x_in = xg[0].cpu().double().numpy() if layer == target else None
+                gpu.block(layer, xg, e0g, [desc])
+                if layer != target:
+                    continue
+                dbg = {}
+                xo = ora.block(layer, x_in, e0o, desc, debug=dbg)
+                upd_o = xo - x_in
+                err = max_rel_err(xg[0].cpu().double().numpy() - x_in, upd_o)
+                floor = branch_floor(dbg)
+                print("layer %d chunk %d: update err %.3e, max |x_in| %.1f, max |update| %.2f, smallest branch %.2f"
+                      % (layer, chunk, err, np.abs(x_in).max(), np.abs(upd_o).max(), floor), flush=True)
+                assert floor >= 5 * TOL_X * np.abs(xo).max(), (chunk, layer, floor)
+                assert err <= TOL_X, (chunk, layer, err)
+                assert gpu.state(layer, 0) == ora.caches[layer][0].state()
+                assert np.array_equal(gpu.slot_map(layer, 0), ora.caches[layer][0].slot_map())
+        assert ora.caches[target][0].state()["evicted"] > 0
+        for k, v in plain.items():
+            gpu.layers[target][k].copy_(v)
+        del ora
+    gpu.close()
+
+
+def staggered_480p_self_attention(wl, follow):
+    """Four streams that start one round apart, batched in one call per round, with the self-attention branch as the
+    block's only addition: the oracle follows the streams in `follow`; each stream's update is compared relative to
+    itself, so a stream that read another stream's cache, or a key range of the wrong length, fails."""
+    gpu = GpuRunner(wl, n_layers=1, n_streams=4, edit=self_attention_alone)
+    ora = OracleRunner(wl, n_layers=1, n_streams=4, edit=self_attention_alone)
+    for rnd in range(4):
+        active = [s for s in range(4) if rnd >= s]
+        descs = [(s, (rnd - s) * wl.frames_per_chunk, wl.frames_per_chunk, 1) for s in active]
+        xs = [wk.chunk_input(wl, rnd - s, s) for s in active]
+        e0s = [caller_e0(wl, rnd - s, s, zero_rows=(2, 5)) for s in active]
+        xg = torch.stack(xs).to(gpu.device).contiguous()
+        gpu.block(0, xg, torch.stack(e0s).to(gpu.device).contiguous(), descs)
+        torch.cuda.synchronize()
+        for i, s in enumerate(active):
+            if s not in follow:
+                continue
+            x_in = xs[i].double().numpy()
+            upd_o = ora.block(0, x_in, e0s[i].double().numpy(), descs[i]) - x_in
+            err = max_rel_err(xg[i].cpu().double().numpy() - x_in, upd_o)
+            print("round %d stream %d: update err %.3e" % (rnd, s, err), flush=True)
+            assert err <= TOL_X, (rnd, s, err)
+            assert gpu.state(0, s) == ora.caches[0][s].state(), (rnd, s)
+    gpu.close()
+
+
+@pytest.mark.timeout(900)
+def test_480p_geometry_staggered_batch_self_attention_alone():
+    """The batched 480p schedule at its real token counts on a narrow model, every stream followed."""
+    wl = wk.Workload("480p-narrow", C=256, H=2, F=512, grid_h=30, grid_w=52, frames_per_chunk=3, sink_frames=1,
+                     window_frames=6, L_t=512, B=4, N=1, steps=(1,), chunks=4)
+    staggered_480p_self_attention(wl, follow=(0, 1, 2, 3))
 
 
 @pytest.mark.timeout(900)
@@ -201,12 +372,12 @@ def test_480p_geometry_staggered_batch_of_four():
 def test_wan14b_480p_block_staggered_streams():
     """One block of the batched 480p workload at full width (C 5120, 40 heads, FFN 13824; 4680 tokens per chunk,
     up to 10920 keys): four rounds in which streams 0 .. 3 join one after the other, the last with all four in one
-    call (18720 rows).  The oracle follows stream 0 through warm-up, its first eviction, whose append wraps inside
+    call (18720 rows), with gates of order one so that every branch shows at the output.  The oracle follows stream 0 through warm-up, its first eviction, whose append wraps inside
     the chunk, and one steady-state chunk; the other streams' cache state is checked against the oracle's cache
     class."""
     wl = wk.WORKLOADS["wan14b-480p-b4"]
-    gpu = GpuRunner(wl, n_layers=1, n_streams=4)
-    ora = OracleRunner(wl, n_layers=1, n_streams=1)
+    gpu = GpuRunner(wl, n_layers=1, n_streams=4, edit=visible_branches(wl))
+    ora = OracleRunner(wl, n_layers=1, n_streams=1, edit=visible_branches(wl))
     shadow = {s: oracle.RollingKVCache(wl.S, wl.W, wl.P, 1) for s in (1, 2, 3)}
     for rnd in range(4):
         active = [s for s in range(4) if rnd >= s]
@@ -216,9 +387,12 @@ def test_wan14b_480p_block_staggered_streams():
         xg = torch.stack(xs).to(gpu.device).contiguous()
         gpu.denoise(xg, descs, timesteps=ts)
         torch.cuda.synchronize()
-        xo = ora.denoise(xs[0].double().numpy(), descs[0], timestep=ts[0])
+        dbg = {}
+        xo = ora.denoise(xs[0].double().numpy(), descs[0], timestep=ts[0], debug=dbg)
         err = max_rel_err(xg[0].cpu().numpy(), xo)
-        print("round %d: stream 0 max rel err %.3e" % (rnd, err), flush=True)
+        print("round %d: stream 0 max rel err %.3e, smallest branch %.2f of max |x| %.2f"
+              % (rnd, err, branch_floor(dbg), np.abs(xo).max()), flush=True)
+        assert branch_floor(dbg) >= 5 * TOL_X * np.abs(xo).max(), "a branch hides below the tolerance"
         assert err <= TOL_X, (rnd, err)
         for s in active:
             if s in shadow:
