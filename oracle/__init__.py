@@ -14,6 +14,7 @@ What it follows (StreamDiffusionV2):
   * the adaptive sink refresh and the RoPE refresh (Section 4.1), in ``refresh.py``;
   * the motion-aware noise scheduler (Section 4.1), in ``motion.py``;
   * the SLO-aware batching scheduler (Section 4.1), in ``slo.py``;
+  * the stream batch over denoising steps (Section 4.2), in ``stream_batch.py``;
   * a causal DiT of the Wan 2.1 / CausVid lineage (Section 5.1 "Models") whose
     per-layer cost is 24 b L_q C^2 + 4 b L_q L_kv C (Appendix B).
 
@@ -37,6 +38,7 @@ from .refresh import (  # noqa: F401
     rotate_keys,
 )
 from .slo import latency_model, frequency, pick_batch  # noqa: F401
+from .stream_batch import StreamBatch  # noqa: F401
 from .motion import (  # noqa: F401
     motion_intensity,
     normalized_motion,
