@@ -71,21 +71,29 @@ def main():
     ms_per_step, wall_ms, kernels, roofline = m["ms_per_step"], m["wall_ms"], m["kernels"], m["roofline"]
     step_flops, gemm_tflops, attn_tflops, l_kv = m["step_flops"], m["gemm_tflops"], m["attn_tflops"], m["l_kv"]
     B, L, Cw = wl.B, wl.L, wl.C
+    peaks = measure_peaks()
+    add_measured_fractions(roofline, peaks)
     also = None
-    if not args.no_also and args.workload != "wan14b-step":
-        m2 = measure("wan14b-step", 8, 2, 0)
-        w2 = wk.WORKLOADS["wan14b-step"]
-        also = {"wan14b-step": {
-            "workload": "40 blocks, C %d, %d heads x 128, FFN %d, 1 stream x %d query tokens per chunk, L_kv %d, %d text "
-                        "tokens, 1 denoising step per chunk" % (w2.C, w2.H, w2.F, w2.L, m2["l_kv"], w2.L_t),
-            "value": round(m2["ms_per_step"], 4), "unit": "ms", "steps": 8, "warmup": 2,
-            "step_tflops": round(m2["step_flops"] / (m2["ms_per_step"] * 1e-3) / 1e12, 1),
-            "step_frac_mfma_peak": round(m2["step_flops"] / (m2["ms_per_step"] * 1e-3) / cm.MI355X_BF16_FLOPS, 4),
-            "gemm_tflops": round(m2["gemm_tflops"], 1), "attn_tflops": round(m2["attn_tflops"], 1),
-            "kernels": m2["kernels"]}}
-
     if not args.no_also:
-        also = dict(also or {})
+        also = {}
+        for name, k_steps, k_warm in (("wan14b-step", 8, 2), ("wan14b-480p-b4", 2, 1)):
+            if name == args.workload:
+                continue
+            m2 = measure(name, k_steps, k_warm, 0)
+            w2 = wk.WORKLOADS[name]
+            add_measured_fractions(m2["roofline"], peaks)
+            frac = m2["step_flops"] / (m2["ms_per_step"] * 1e-3) / cm.MI355X_BF16_FLOPS
+            also[name] = {
+                "workload": "%d blocks, C %d, %d heads x 128, FFN %d, %d stream(s) x %d query tokens per chunk, L_kv %d, "
+                            "%d text tokens, 1 denoising step per chunk" % (w2.N, w2.C, w2.H, w2.F, w2.B, w2.L, m2["l_kv"], w2.L_t),
+                "value": round(m2["ms_per_step"], 4), "unit": "ms", "steps": k_steps, "warmup": k_warm,
+                "wall_ms_per_step": round(m2["wall_ms"], 4),
+                "step_tflops": round(m2["step_flops"] / (m2["ms_per_step"] * 1e-3) / 1e12, 1),
+                "step_frac_mfma_peak": round(frac, 4),
+                "step_frac_measured_mfma_peak": round(frac * cm.MI355X_BF16_FLOPS / (peaks["mfma_bf16"]["measured"] * 1e12), 4),
+                "gemm_tflops": round(m2["gemm_tflops"], 1), "attn_tflops": round(m2["attn_tflops"], 1),
+                "roofline": m2["roofline"], "kernels": m2["kernels"]}
+        also["stream_batch"] = measure_stream_batch(args.workload) if args.workload == "wan1.3b-step" else None
         also["refresh"] = measure_refresh(args.workload)
         also["motion"] = measure_motion()
 
@@ -108,9 +116,55 @@ def main():
         "step_tflops": round(step_flops / (ms_per_step * 1e-3) / 1e12, 1),
         "step_frac_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / cm.MI355X_BF16_FLOPS, 4),
         "gemm_tflops": round(gemm_tflops, 1), "attn_tflops": round(attn_tflops, 1),
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "latency": m["latency"], "also": also,
+        "step_frac_measured_mfma_peak": round(step_flops / (ms_per_step * 1e-3) / (peaks["mfma_bf16"]["measured"] * 1e12), 4),
+        "roofline": roofline, "peaks": peaks, "cpu_baseline": cpu_baseline, "kernels": kernels, "latency": m["latency"],
+        "also": also,
     }
     print(json.dumps(out))
+
+
+def measure_peaks():
+    """What the chip sustains, beside the published peaks: a register-resident loop of bf16 matrix instructions on
+    every compute unit (no memory traffic) and a streaming copy of 1 GiB (read + write), each the best of five
+    launches between events on the launch stream."""
+    import torch
+    from paper_2511_07399_amd import binding, cost_model as cm
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    wgs, iters = 256 * 4, 4096
+    sink = torch.empty(wgs * 512, dtype=torch.float32, device=dev)
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+
+    def best(fn, reps=5):
+        fn()
+        out = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            work = fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            out.append(work / (e0.elapsed_time(e1) * 1e-3))
+        return max(out)
+
+    mfma = best(lambda: binding.prof_peak_mfma(iters, wgs, sink))
+    copy = best(lambda: 2 * binding.prof_peak_copy(src, dst))
+    assert torch.equal(src[:4096], dst[:4096]) and torch.equal(src[-4096:], dst[-4096:])
+    del src, dst, sink
+    torch.cuda.empty_cache()
+    return {
+        "mfma_bf16": {"published": cm.MI355X_BF16_FLOPS / 1e12, "measured": round(mfma / 1e12, 1), "unit": "TFLOP/s",
+                      "how": "v_mfma_f32_32x32x16_bf16 on register operands, 8 independent accumulators per wave, "
+                             "8 waves per workgroup, %d workgroups x %d iterations" % (wgs, iters)},
+        "hbm_copy": {"published": cm.MI355X_HBM_BW / 1e9, "measured": round(copy / 1e9, 1), "unit": "GB/s",
+                     "how": "1 GiB device copy, 16-byte accesses, read + write bytes counted"},
+    }
+
+
+def add_measured_fractions(roofline, peaks):
+    roofline["peak_measured"] = peaks["mfma_bf16"]["measured"]
+    roofline["frac_of_measured_peak"] = round(roofline["achieved"] / peaks["mfma_bf16"]["measured"], 4)
 
 
 def measure(workload, steps, warmup, copy_calibration, n_dist=0):
@@ -209,15 +263,27 @@ def measure(workload, steps, warmup, copy_calibration, n_dist=0):
     sum_us = lambda tags: sum(float(np.mean(per_tag[t])) * 1e3 for t in tags if t in per_tag)
     gemm_tflops = sum(flops[t] for t in gemm_tags) / (sum_us(gemm_tags) * 1e-6) / 1e12
     attn_tflops = sum(flops[t] for t in attn_tags) / (sum_us(attn_tags) * 1e-6) / 1e12
-    # dominant kernel: the FFN-1 GEMM launch site (largest share of the block's flops)
-    dom = 11
-    dom_us = float(np.mean(per_tag[dom])) * 1e3
-    achieved = flops[dom] / (dom_us * 1e-6) / 1e12
+    # Dominant kernel = the group of launch sites that run the same kernel on the same shape and take the largest
+    # share of the step (the three C x C projections are one group: same kernel, same M, N, K).
+    groups = {
+        "C x C projection GEMM (out-proj, cross-q, cross-out; M=%d, N=%d, K=%d, bf16)" % (rows, Cw, Cw): (4, 6, 9),
+        "QKV GEMM (M=%d, N=%d, K=%d, bf16)" % (rows, 3 * Cw, Cw): (1,),
+        "FFN-1 GEMM (M=%d, N=%d, K=%d, bf16, GELU epilogue)" % (rows, wl.F, Cw): (11,),
+        "FFN-2 GEMM (M=%d, N=%d, K=%d, bf16, gated residual)" % (rows, Cw, wl.F): (12,),
+        "self-attention over the rolling cache (%d queries x %d keys x %d heads, bf16)" % (rows, l_kv, wl.H): (3,),
+        "text cross-attention (%d queries x %d keys x %d heads, bf16)" % (rows, wl.L_t, wl.H): (8,),
+    }
+    all_us = sum_us(per_tag.keys())
+    dom_name, dom_tags = max(groups.items(), key=lambda kv: sum_us(kv[1]))
+    dom_us = sum_us(dom_tags) / len(dom_tags)                       # average duration of one launch of the group
+    dom_flops = flops[dom_tags[0]]
+    achieved = dom_flops / (dom_us * 1e-6) / 1e12
     roofline = {
-        "bound": "mfma", "kernel": "gemm_kernel @ FFN-1 (M=%d, N=%d, K=%d, bf16)" % (rows, wl.F, Cw),
+        "bound": "mfma", "kernel": dom_name, "launch_sites": [binding.LAUNCH_TAGS[t] for t in dom_tags],
+        "share_of_step_time": round(sum_us(dom_tags) / all_us, 4),
         "achieved": round(achieved, 1), "peak": cm.MI355X_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
         "frac": round(achieved * 1e12 / cm.MI355X_BF16_FLOPS, 4), "avg_launch_us": round(dom_us, 2),
-        "flops_per_launch": flops[dom], "traffic": load_traffic(wl.name, "FFN-1 gemm"),
+        "flops_per_launch": dom_flops, "traffic": load_traffic(wl.name, dom_name.split(" (")[0]),
     }
     step_flops = wl.N * cm.block_flops(rows, Cw, wl.F, l_kv, wl.L_t)
     latency = None
@@ -302,6 +368,67 @@ def batch_sweep(workload, sizes, steps, warmup):
             "picks": picks}
 
 
+def measure_stream_batch(workload, depths=(2, 4), steps=12):
+    """Stream batch over denoising steps (Section 4.2): one stream denoised in n steps per chunk runs as n batch rows
+    at n noise depths, each depth with its own rolling cache, one batched denoise step per micro-step and one
+    finished chunk per micro-step.  Steady state (pipeline full, every depth cache full and evicting): latency of a
+    micro-step, which is also the time between finished chunks, and the same per batch row."""
+    import dataclasses
+    import torch
+    from paper_2511_07399_amd import binding, cost_model as cm, workloads as wk
+    from paper_2511_07399_amd.runner import DeviceModel
+    base = wk.WORKLOADS[workload]
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    out = {}
+    for n in depths:
+        wl = dataclasses.replace(base, name="%s/n%d" % (base.name, n), B=n)
+        gpu = DeviceModel(wl, base_seed=0, device=dev, weight_device=dev)
+        kt = binding.ptr_array([gpu.kt[layer][0] for layer in range(wl.N)])
+        vtt = binding.ptr_array([gpu.vtt[layer][0] for layer in range(wl.N)])
+        rows = torch.empty(binding.stream_batch_rows_bytes(gpu.cfg, n, wl.frames_per_chunk), dtype=torch.uint8, device=dev)
+        sb = binding.stream_batch_create(gpu.cfg, n, list(range(n)), wl.frames_per_chunk, rows)
+        ws = gpu.workspace(n, wl.L)
+        xs = [wk.chunk_input(wl, c, 0, device=dev) for c in range(4)]
+        x_out = torch.empty(wl.L, wl.C, dtype=torch.float32, device=dev)
+        ts = [1000.0 * (n - d) / (n + 1) for d in range(n)]             # a fixed schedule, noisiest first
+        fill = (wl.sink_frames + wl.window_frames) // wl.frames_per_chunk + n + 2
+        m = 0
+        for _ in range(fill):
+            binding.stream_batch_step(sb, gpu.cfg, gpu.mw, gpu.cache, xs[m % 4], m * wl.frames_per_chunk, ts, kt, vtt, x_out, ws)
+            m += 1
+        torch.cuda.synchronize()
+        st = gpu.state(wl.N - 1, n - 1)
+        assert st["win_fill"] == wl.W and st["evicted"] > 0, "deepest cache not at steady state"
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        emitted = 0
+        for _ in range(steps):
+            e, r = binding.stream_batch_step(sb, gpu.cfg, gpu.mw, gpu.cache, xs[m % 4], m * wl.frames_per_chunk, ts, kt, vtt, x_out, ws)
+            assert r == n
+            emitted += int(e)
+            m += 1
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        ms = ev0.elapsed_time(ev1) / steps
+        assert emitted == steps and bool(torch.isfinite(x_out).all())
+        l_kv = st["sink_fill"] + st["win_fill"]
+        flops = wl.N * cm.block_flops(n * wl.L, wl.C, wl.F, l_kv, wl.L_t)
+        out["%d steps per chunk" % n] = {
+            "batch_rows": n, "ms_per_micro_step": round(ms, 4), "wall_ms_per_micro_step": round(wall, 4),
+            "ms_per_row": round(ms / n, 4), "finished_chunks_per_s": round(1e3 / ms, 1),
+            "step_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+            "step_frac_mfma_peak": round(flops / (ms * 1e-3) / cm.MI355X_BF16_FLOPS, 4)}
+        binding.stream_batch_destroy(sb)
+        gpu.close()
+        del gpu, rows, ws, xs
+        torch.cuda.empty_cache()
+    return {"workload": "%s, one stream, n denoising steps per chunk as n batch rows at n noise depths (own cache per "
+                        "depth), steady state, %d timed micro-steps" % (base.name, steps), "depths": out}
+
+
 def measure_refresh(workload, reps=20):
     """The three cache-refresh operations (sink similarity, sink copy, key move) on ONE (layer, stream) cache of the
     workload's geometry at steady state: average launch time over `reps` launches and the rate on their
@@ -383,7 +510,8 @@ def measure_motion(reps=20):
 
 def load_traffic(workload, launch_site):
     """HBM bytes per launch of the dominant kernel, as derived from the rocprofv3 --pmc runs whose summary
-    is committed under profiles/ (null when no such measurement is recorded for this workload)."""
+    is committed under profiles/ (null when no such measurement is recorded for this kernel of this workload:
+    counters cannot be read from inside the timed run)."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:

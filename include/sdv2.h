@@ -347,6 +347,46 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
                           void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Stream batch over denoising steps (Section 1, contribution (1): inputs reformulated as a batch of short chunks;
+ * Section 4.2 and its pipeline-parallel stream-batch figure: the n denoising steps of a chunk act as a batch
+ * multiplier, L(T, n B), the rows are latent streams at different noise levels, and a clean latent leaves at every
+ * micro-step; Section 5.4: more steps, deeper pipeline).
+ *
+ * The paper prints no schedule; this library takes: a stream denoised in n_steps steps per chunk keeps n_steps chunks
+ * in flight.  One micro-step = the newest chunk enters at depth 0, every in-flight chunk makes one denoising step at
+ * its depth d with timesteps_host[d], all of them in ONE batched sdv2_denoise_step (n_steps rows in steady state),
+ * and the chunk that has finished depth n_steps - 1 leaves.  Each depth has its own rolling cache stream
+ * (cache_stream_ids[d], distinct): what a chunk writes at depth d is the history that the following chunks read at
+ * depth d.  Chunk c leaves at micro-step c + n_steps - 1.  The rotation is by index: a chunk stays in the row of
+ * `rows_dev` it entered until it leaves; only the entering and the leaving chunk are copied ([L, C] fp32 each).
+ *
+ * sdv2_stream_batch_create: rows_dev = caller-owned fp32 [n_steps][L][C] (256-byte aligned,
+ *   sdv2_stream_batch_rows_bytes), L = n_frames * tokens_per_frame.  The cache handle passed to the steps must have
+ *   every cache_stream_ids[d] as a stream.  _destroy frees the host handle; _reset empties the pipeline (host only;
+ *   resetting the cache streams is the caller's).
+ * sdv2_stream_batch_step: x_in_dev = the entering chunk's hidden state (dev fp32 [L, C]) with its RoPE frame index
+ *   frame_pos0, or NULL when nothing enters (the pipeline drains: the occupied rows may then form two runs in memory
+ *   and the micro-step issues two batched calls).  kt_dev / vtt_dev: host arrays [n_layers] of this stream's text
+ *   K/V.  *emitted_out = 1 when a chunk left, its hidden state then being in x_out_dev (dev fp32 [L, C]);
+ *   *rows_out (optional) = batch rows of this micro-step.  Workspace: sdv2_denoise_workspace_bytes(cfg, n_steps, L).
+ *   Asynchronous on hip_stream like every other call.
+ * Errors: as sdv2_denoise_step; n_steps outside 1 .. SDV2_MAX_BATCH, repeated cache stream ids: SDV2_INVALID_ARG.
+ *   If a launch fails after part of a micro-step has run, the handle refuses further steps (SDV2_BAD_STATE) until
+ *   sdv2_stream_batch_reset.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct sdv2_stream_batch sdv2_stream_batch;   /* opaque host handle */
+size_t sdv2_stream_batch_rows_bytes(const sdv2_model_cfg* cfg, int32_t n_steps, int32_t n_frames);
+int32_t sdv2_stream_batch_create(const sdv2_model_cfg* cfg, int32_t n_steps, const int32_t* cache_stream_ids,
+                                 int32_t n_frames, float* rows_dev, size_t rows_bytes, sdv2_stream_batch** out);
+int32_t sdv2_stream_batch_destroy(sdv2_stream_batch* sb);
+int32_t sdv2_stream_batch_reset(sdv2_stream_batch* sb);
+int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw,
+                               sdv2_kv_cache* cache, const float* x_in_dev, int32_t frame_pos0,
+                               const float* timesteps_host, const void* const* kt_dev, const void* const* vtt_dev,
+                               float* x_out_dev, int32_t* emitted_out, int32_t* rows_out,
+                               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
  * The two dense kernels on their own (used by the per-kernel parity tests and the benchmark).
  *
  * sdv2_gemm_bf16: out = epilogue(a W^T + bias).  a: bf16 [M, K]; w: bf16 [N, K]; bias fp32 [N] or NULL.
@@ -391,6 +431,30 @@ enum sdv2_launch_tag {
 };
 int32_t sdv2_prof_begin(int32_t max_samples);
 int32_t sdv2_prof_end(int32_t* tags_out, float* ms_out, int32_t capacity, int32_t* n_out);
+
+/* ------------------------------------------------------------------------------------------------
+ * What the chip sustains, measured by the benchmark beside the published peaks (not part of the streaming path).
+ * sdv2_prof_peak_mfma: `workgroups` workgroups of eight waves, each wave issuing iters x 8 independent
+ *   v_mfma_f32_32x32x16_bf16 on register operands (no memory traffic); *flops_out = the flops of the launch
+ *   (2 x 32 x 32 x 16 per instruction).  sink_dev: dev fp32 [workgroups * 512], written once at the end.
+ * sdv2_prof_peak_copy: dst <- src, `bytes` (multiple of 16) bytes, 16-byte accesses, grid-stride; moves 2 x bytes
+ *   through HBM when the buffers exceed the caches.
+ * Both only enqueue one kernel; the caller times it with events on the same stream.
+ * ------------------------------------------------------------------------------------------------ */
+int32_t sdv2_prof_peak_mfma(int32_t iters, int32_t workgroups, float* sink_dev, size_t sink_floats, double* flops_out,
+                            void* hip_stream);
+int32_t sdv2_prof_peak_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Tuning hook for tests and sweeps (not for production use, not thread safe): replaces the library's own choice of
+ * a kernel plan until cleared with value NULL or "".  It changes workspace sizes too, so set it before the
+ * *_workspace_bytes query that goes with a call.  Nothing is read from the environment.
+ *   "gemm_tile":   "tm,tn[,pf[,k_parts]]" (register-staged kernel, tile 128 tm x 32 tn) or "d<id>[,k_parts]"
+ *                  (a configuration of the direct-to-LDS kernel)
+ *   "attn_waves":  "4" or "8" waves per attention workgroup;  "attn_splits": parts of the key range (1 .. 16)
+ * Errors: unknown name or a value that does not parse: SDV2_INVALID_ARG (the previous setting stays).
+ * ------------------------------------------------------------------------------------------------ */
+int32_t sdv2_tuning_set(const char* name, const char* value);
 
 #ifdef __cplusplus
 }

@@ -74,6 +74,9 @@ EXPORTS = (
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
     "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
+    "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_tuning_set",
+    "sdv2_stream_batch_rows_bytes", "sdv2_stream_batch_create", "sdv2_stream_batch_destroy",
+    "sdv2_stream_batch_reset", "sdv2_stream_batch_step",
 )
 
 LAUNCH_TAGS = ("adaLN-1", "QKV gemm", "rope+append", "self-attn", "out-proj gemm", "LN-3", "cross-q gemm",
@@ -142,6 +145,17 @@ def load_library():
                                         i32, i32, vp, sz, vp]
     lib.sdv2_prof_begin.argtypes = [i32]
     lib.sdv2_prof_end.argtypes = [C.POINTER(i32), C.POINTER(C.c_float), i32, C.POINTER(i32)]
+    lib.sdv2_prof_peak_mfma.argtypes = [i32, i32, f32p, sz, C.POINTER(C.c_double), vp]
+    lib.sdv2_prof_peak_copy.argtypes = [vp, vp, sz, vp]
+    lib.sdv2_tuning_set.argtypes = [C.c_char_p, C.c_char_p]
+    lib.sdv2_stream_batch_rows_bytes.restype = sz
+    lib.sdv2_stream_batch_rows_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
+    lib.sdv2_stream_batch_create.argtypes = [C.POINTER(ModelCfg), i32, C.POINTER(i32), i32, f32p, sz, C.POINTER(vp)]
+    lib.sdv2_stream_batch_destroy.argtypes = [vp]
+    lib.sdv2_stream_batch_reset.argtypes = [vp]
+    lib.sdv2_stream_batch_step.argtypes = [vp, C.POINTER(ModelCfg), C.POINTER(ModelWeights), vp, f32p, i32,
+                                           C.POINTER(C.c_float), C.POINTER(vp), C.POINTER(vp), f32p, C.POINTER(i32),
+                                           C.POINTER(i32), vp, sz, vp]
     _lib = lib
     return lib
 
@@ -444,3 +458,63 @@ def prof_end(capacity):
     n = C.c_int32()
     _check(_lib.sdv2_prof_end(tags, ms, capacity, C.byref(n)))
     return [(tags[i], ms[i]) for i in range(n.value)]
+
+
+def prof_peak_mfma(iters, workgroups, sink):
+    """Enqueues the register-resident matrix-instruction loop; returns the flops of the launch."""
+    load_library()
+    _dev(sink, torch.float32)
+    flops = C.c_double()
+    _check(_lib.sdv2_prof_peak_mfma(iters, workgroups, _ptr(sink), sink.numel(), C.byref(flops), _stream()))
+    return flops.value
+
+
+def prof_peak_copy(src, dst):
+    load_library()
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(_lib.sdv2_prof_peak_copy(_ptr(src), _ptr(dst), n, _stream()))
+    return n
+
+
+def tuning_set(name, value=None):
+    """Test / sweep hook: force a kernel plan ("gemm_tile", "attn_waves", "attn_splits"); None clears it."""
+    load_library()
+    _check(_lib.sdv2_tuning_set(name.encode(), None if value is None else str(value).encode()))
+
+
+# ------------------------------------------------------------------------------------------ stream batch
+def stream_batch_rows_bytes(cfg, n_steps, n_frames):
+    load_library()
+    return int(_lib.sdv2_stream_batch_rows_bytes(C.byref(cfg), n_steps, n_frames))
+
+
+def stream_batch_create(cfg, n_steps, cache_stream_ids, n_frames, rows):
+    """rows: uint8 device tensor of stream_batch_rows_bytes bytes that the caller keeps alive."""
+    load_library()
+    ids = (C.c_int32 * n_steps)(*cache_stream_ids)
+    h = C.c_void_p()
+    _check(_lib.sdv2_stream_batch_create(C.byref(cfg), n_steps, ids, n_frames, _ptr(rows),
+                                         rows.numel() * rows.element_size(), C.byref(h)))
+    return h
+
+
+def stream_batch_destroy(h):
+    _check(_lib.sdv2_stream_batch_destroy(h))
+
+
+def stream_batch_reset(h):
+    _check(_lib.sdv2_stream_batch_reset(h))
+
+
+def stream_batch_step(h, cfg, mw, cache, x_in, frame_pos0, timesteps, kt, vtt, x_out, workspace):
+    """kt / vtt: ctypes pointer arrays [n_layers].  Returns (emitted, rows)."""
+    if x_in is not None:
+        _dev(x_in, torch.float32)
+    _dev(x_out, torch.float32)
+    ts = (C.c_float * len(timesteps))(*timesteps)
+    emitted, rows = C.c_int32(), C.c_int32()
+    _check(_lib.sdv2_stream_batch_step(h, C.byref(cfg), C.byref(mw), cache, _ptr(x_in), frame_pos0, ts, kt, vtt,
+                                       _ptr(x_out), C.byref(emitted), C.byref(rows), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream()))
+    return bool(emitted.value), rows.value

@@ -5,8 +5,10 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -142,7 +144,28 @@ AppendStream append_stream(const sdv2_kv_cache* c, int layer, int stream, int64_
 extern "C" {
 
 const char* sdv2_last_error(void) { return g_last_error.c_str(); }
-int32_t sdv2_version(void) { return 1; }
+int32_t sdv2_version(void) { return 2; }
+
+int32_t sdv2_tuning_set(const char* name, const char* value) {
+    if (!name) return fail(SDV2_INVALID_ARG, "name is null");
+    const bool clear = !value || !*value;
+    if (!strcmp(name, "gemm_tile")) {
+        if (!set_gemm_tile_override(clear ? nullptr : value)) return fail(SDV2_INVALID_ARG, "gemm_tile \"%s\" not understood", value);
+        return SDV2_OK;
+    }
+    if (!strcmp(name, "attn_waves") || !strcmp(name, "attn_splits")) {
+        const int v = clear ? 0 : atoi(value);
+        if (v < 0) return fail(SDV2_INVALID_ARG, "%s must be >= 0", name);
+        if (!strcmp(name, "attn_waves")) {
+            if (v != 0 && v != 4 && v != 8) return fail(SDV2_INVALID_ARG, "attn_waves must be 0, 4 or 8");
+            set_attention_overrides(v, -1);
+        } else {
+            set_attention_overrides(-1, v);
+        }
+        return SDV2_OK;
+    }
+    return fail(SDV2_INVALID_ARG, "unknown tuning name \"%s\"", name);
+}
 
 size_t sdv2_kv_cache_bytes(const sdv2_cache_cfg* cfg) {
     const char* why;
@@ -1020,11 +1043,196 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
                                    sdv2_conditioning_workspace_bytes(cfg, B), hip_stream);
     if (rc) return rc;
     const BlockWorkspace ws = carve_block(cfg, B, L, max_kv_possible(cache), p);
+    // Ring positions of every layer of the listed streams, to put back if a launch fails half way: the layers that
+    // already ran would otherwise sit one chunk ahead of the others.  (x and the cache contents of those layers have
+    // been overwritten by then; the call reports the failing layer.)
+    std::vector<int64_t> total0((size_t)cfg->n_layers * B);
+    std::vector<int32_t> last0((size_t)cfg->n_layers * B);
+    for (int layer = 0; layer < cfg->n_layers; ++layer)
+        for (int b = 0; b < B; ++b) {
+            const size_t idx = (size_t)layer * cache->cfg.n_streams + chunks[b].stream_id;
+            total0[(size_t)layer * B + b] = cache->total[idx];
+            last0[(size_t)layer * B + b] = cache->last_n[idx];
+        }
     for (int layer = 0; layer < cfg->n_layers; ++layer) {
         rc = run_block(cfg, &mw->blocks[layer], cache, layer, x_dev, e0, kt_dev + (size_t)layer * B,
                        vtt_dev + (size_t)layer * B, chunks, B, L, ws, s);
-        if (rc) return rc;
+        if (rc) {
+            for (int l2 = 0; l2 < layer; ++l2)
+                for (int b = 0; b < B; ++b) {
+                    const size_t idx = (size_t)l2 * cache->cfg.n_streams + chunks[b].stream_id;
+                    cache->total[idx] = total0[(size_t)l2 * B + b];
+                    cache->last_n[idx] = last0[(size_t)l2 * B + b];
+                }
+            const std::string inner = g_last_error;
+            return fail(rc, "layer %d: %s", layer, inner.c_str());
+        }
     }
+    return SDV2_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------ stream batch over denoising steps
+struct sdv2_stream_batch {
+    int n_steps, n_frames;
+    size_t row_floats;                 // L * C
+    float* x_pipe;                     // [n_steps][L][C], caller-owned
+    int32_t cache_ids[SDV2_MAX_BATCH]; // cache stream of each depth
+    int depth[SDV2_MAX_BATCH];         // per pipeline row: depth of the chunk it holds, -1 = free
+    int32_t frame_pos0[SDV2_MAX_BATCH];
+    int64_t entered;                   // chunks that have entered
+    bool broken;
+};
+
+extern "C" {
+
+size_t sdv2_stream_batch_rows_bytes(const sdv2_model_cfg* cfg, int32_t n_steps, int32_t n_frames) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why) || n_steps < 1 || n_steps > SDV2_MAX_BATCH || n_frames < 1) {
+        fail(SDV2_INVALID_ARG, "bad cfg, n_steps or n_frames");
+        return 0;
+    }
+    return align_up((size_t)n_steps * n_frames * cfg->grid_h * cfg->grid_w * cfg->C * sizeof(float), 256);
+}
+
+int32_t sdv2_stream_batch_create(const sdv2_model_cfg* cfg, int32_t n_steps, const int32_t* cache_stream_ids,
+                                 int32_t n_frames, float* rows_dev, size_t rows_bytes, sdv2_stream_batch** out) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (n_steps < 1 || n_steps > SDV2_MAX_BATCH) return fail(SDV2_INVALID_ARG, "n_steps = %d outside 1 .. %d", n_steps, SDV2_MAX_BATCH);
+    if (n_frames < 1) return fail(SDV2_INVALID_ARG, "n_frames must be positive");
+    if (!cache_stream_ids || !rows_dev || !out) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (reinterpret_cast<uintptr_t>(rows_dev) % 256) return fail(SDV2_INVALID_ARG, "rows_dev must be 256-byte aligned");
+    for (int d = 0; d < n_steps; ++d) {
+        if (cache_stream_ids[d] < 0) return fail(SDV2_INVALID_ARG, "cache stream id of depth %d is negative", d);
+        for (int e = 0; e < d; ++e)
+            if (cache_stream_ids[e] == cache_stream_ids[d])
+                return fail(SDV2_INVALID_ARG, "depths %d and %d name the same cache stream", e, d);
+    }
+    const size_t need = sdv2_stream_batch_rows_bytes(cfg, n_steps, n_frames);
+    if (rows_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "rows buffer %zu < %zu", rows_bytes, need);
+    sdv2_stream_batch* sb = new (std::nothrow) sdv2_stream_batch;
+    if (!sb) return fail(SDV2_INVALID_ARG, "out of host memory");
+    sb->n_steps = n_steps;
+    sb->n_frames = n_frames;
+    sb->row_floats = (size_t)n_frames * cfg->grid_h * cfg->grid_w * cfg->C;
+    sb->x_pipe = rows_dev;
+    for (int d = 0; d < SDV2_MAX_BATCH; ++d) {
+        sb->cache_ids[d] = d < n_steps ? cache_stream_ids[d] : -1;
+        sb->depth[d] = -1;
+        sb->frame_pos0[d] = 0;
+    }
+    sb->entered = 0;
+    sb->broken = false;
+    *out = sb;
+    return SDV2_OK;
+}
+
+int32_t sdv2_stream_batch_destroy(sdv2_stream_batch* sb) {
+    delete sb;
+    return SDV2_OK;
+}
+
+int32_t sdv2_stream_batch_reset(sdv2_stream_batch* sb) {
+    if (!sb) return fail(SDV2_INVALID_ARG, "handle is null");
+    for (int r = 0; r < SDV2_MAX_BATCH; ++r) sb->depth[r] = -1;
+    sb->entered = 0;
+    sb->broken = false;
+    return SDV2_OK;
+}
+
+int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw,
+                               sdv2_kv_cache* cache, const float* x_in_dev, int32_t frame_pos0,
+                               const float* timesteps_host, const void* const* kt_dev, const void* const* vtt_dev,
+                               float* x_out_dev, int32_t* emitted_out, int32_t* rows_out, void* workspace_dev,
+                               size_t workspace_bytes, void* hip_stream) {
+    if (!sb) return fail(SDV2_INVALID_ARG, "handle is null");
+    if (sb->broken) return fail(SDV2_BAD_STATE, "an earlier micro-step failed half way: reset the pipeline and the caches");
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!mw || !cache || !timesteps_host || !kt_dev || !vtt_dev || !x_out_dev || !emitted_out || !workspace_dev)
+        return fail(SDV2_INVALID_ARG, "null pointer");
+    if ((size_t)sb->n_frames * cfg->grid_h * cfg->grid_w * cfg->C != sb->row_floats)
+        return fail(SDV2_INVALID_ARG, "cfg differs from the one the pipeline was created with");
+    if (x_in_dev && frame_pos0 < 0) return fail(SDV2_INVALID_ARG, "frame_pos0 < 0");
+    const int n = sb->n_steps;
+    for (int d = 0; d < n; ++d)
+        if (sb->cache_ids[d] >= cache->cfg.n_streams) return fail(SDV2_INVALID_ARG, "cache stream %d of depth %d out of range", sb->cache_ids[d], d);
+    for (int layer = 0; layer < cfg->n_layers; ++layer)
+        if (!kt_dev[layer] || !vtt_dev[layer]) return fail(SDV2_INVALID_ARG, "text K/V of layer %d is null", layer);
+    const int L = sb->n_frames * cfg->grid_h * cfg->grid_w;
+    const size_t need = sdv2_denoise_workspace_bytes(cfg, n, L);
+    if (workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const size_t row_bytes = sb->row_floats * sizeof(float);
+
+    // the entering chunk takes the row that the chunk emitted n micro-steps after it entered has left
+    int new_row = -1;
+    if (x_in_dev) {
+        new_row = (int)(sb->entered % n);
+        if (sb->depth[new_row] >= 0) return fail(SDV2_BAD_STATE, "row %d is still occupied", new_row);
+        HIP_TRY(hipMemcpyAsync(sb->x_pipe + (size_t)new_row * sb->row_floats, x_in_dev, row_bytes, hipMemcpyDeviceToDevice, s),
+                "copy of the entering chunk");
+        sb->depth[new_row] = 0;
+        sb->frame_pos0[new_row] = frame_pos0;
+        sb->entered += 1;
+    }
+    // one batched denoising step per run of occupied rows that is contiguous in memory: one run in steady state and
+    // while the pipeline fills, at most two while it drains
+    int rows = 0;
+    std::vector<const void*> kt, vtt;
+    int r = 0;
+    while (r < n) {
+        if (sb->depth[r] < 0) {
+            ++r;
+            continue;
+        }
+        int r1 = r;
+        while (r1 < n && sb->depth[r1] >= 0) ++r1;
+        const int B = r1 - r;
+        sdv2_chunk_desc descs[SDV2_MAX_BATCH];
+        float ts[SDV2_MAX_BATCH];
+        for (int b = 0; b < B; ++b) {
+            const int d = sb->depth[r + b];
+            descs[b].stream_id = sb->cache_ids[d];
+            descs[b].frame_pos0 = sb->frame_pos0[r + b];
+            descs[b].n_frames = sb->n_frames;
+            descs[b].advance = 1;
+            ts[b] = timesteps_host[d];
+        }
+        kt.assign((size_t)cfg->n_layers * B, nullptr);
+        vtt.assign((size_t)cfg->n_layers * B, nullptr);
+        for (int layer = 0; layer < cfg->n_layers; ++layer)
+            for (int b = 0; b < B; ++b) {
+                kt[(size_t)layer * B + b] = kt_dev[layer];
+                vtt[(size_t)layer * B + b] = vtt_dev[layer];
+            }
+        const int32_t rc = sdv2_denoise_step(cfg, mw, cache, sb->x_pipe + (size_t)r * sb->row_floats, ts, nullptr, kt.data(),
+                                             vtt.data(), descs, B, workspace_dev, workspace_bytes, hip_stream);
+        if (rc) {
+            if (rows == 0 && new_row >= 0) {          // nothing has run: take the entering chunk out again
+                sb->depth[new_row] = -1;
+                sb->entered -= 1;
+            } else if (rows > 0) {
+                sb->broken = true;
+            }
+            return rc;
+        }
+        for (int b = 0; b < B; ++b) sb->depth[r + b] += 1;
+        rows += B;
+        r = r1;
+    }
+    *emitted_out = 0;
+    for (int row = 0; row < n; ++row) {
+        if (sb->depth[row] == n) {                    // finished its last step: the clean latent of this micro-step
+            HIP_TRY(hipMemcpyAsync(x_out_dev, sb->x_pipe + (size_t)row * sb->row_floats, row_bytes, hipMemcpyDeviceToDevice, s),
+                    "copy of the finished chunk");
+            sb->depth[row] = -1;
+            *emitted_out = 1;
+        }
+    }
+    if (rows_out) *rows_out = rows;
     return SDV2_OK;
 }
 
@@ -1032,6 +1240,24 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
 
 // ------------------------------------------------------------------------------------------ profiling helpers
 extern "C" {
+
+int32_t sdv2_prof_peak_mfma(int32_t iters, int32_t workgroups, float* sink_dev, size_t sink_floats, double* flops_out,
+                            void* hip_stream) {
+    if (iters <= 0 || workgroups <= 0 || workgroups > 65536) return fail(SDV2_INVALID_ARG, "iters and workgroups must be positive");
+    if (!sink_dev || sink_floats < (size_t)workgroups * 512)
+        return fail(SDV2_INVALID_ARG, "sink needs %zu floats", (size_t)workgroups * 512);
+    HIP_TRY(launch_peak_mfma(iters, workgroups, sink_dev, static_cast<hipStream_t>(hip_stream)), "peak mfma kernel");
+    if (flops_out) *flops_out = peak_mfma_flops(iters, workgroups);
+    return SDV2_OK;
+}
+
+int32_t sdv2_prof_peak_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream) {
+    if (!src_dev || !dst_dev || bytes == 0 || bytes % 16) return fail(SDV2_INVALID_ARG, "null pointer, or bytes not a positive multiple of 16");
+    if (reinterpret_cast<uintptr_t>(src_dev) % 16 || reinterpret_cast<uintptr_t>(dst_dev) % 16)
+        return fail(SDV2_INVALID_ARG, "buffers must be 16-byte aligned");
+    HIP_TRY(launch_peak_copy(src_dev, dst_dev, bytes, static_cast<hipStream_t>(hip_stream)), "peak copy kernel");
+    return SDV2_OK;
+}
 
 int32_t sdv2_prof_begin(int32_t max_samples) {
     if (max_samples <= 0 || max_samples > (1 << 20)) return fail(SDV2_INVALID_ARG, "max_samples out of range");

@@ -32,6 +32,7 @@
 
 #include <stdlib.h>
 
+#include <mutex>
 #include <type_traits>
 
 namespace sdv2 {
@@ -391,17 +392,24 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
 
 // Waves per workgroup: 4 (128 queries, two workgroups per compute unit) or 8 (256 queries, one workgroup per unit,
 // half the K/V traffic from the L2 per query).
+// Overrides for tuning runs and tests, set through sdv2_tuning_set("attn_waves" / "attn_splits", ...); 0 = the plan's
+// own choice.
+static int g_force_waves = 0;
+static int g_force_splits = 0;
+void set_attention_overrides(int waves, int splits) {
+    if (waves >= 0) g_force_waves = (waves == 4 || waves == 8) ? waves : 0;
+    if (splits >= 0) g_force_splits = splits > 16 ? 16 : splits;
+}
+
 int attention_plan_waves(int B, int L, int H, int max_kv_len) {
-    const char* e = getenv("SDV2_ATTN_WAVES");       // tuning runs and tests; read at every call
-    if (e && (atoi(e) == 4 || atoi(e) == 8)) return atoi(e);
+    if (g_force_waves) return g_force_waves;
     (void)max_kv_len;
     // 256-query workgroups only where they still give at least half of the compute units a workgroup each
     return ((L + 255) / 256) * H * B >= 128 ? 8 : 4;
 }
 
 int attention_plan_splits(int B, int L, int H, int max_kv_len) {
-    const char* e = getenv("SDV2_ATTN_SPLITS");      // tuning runs and tests; read at every call
-    const int forced = e ? atoi(e) : 0;
+    const int forced = g_force_splits;
     const int QT = 32 * attention_plan_waves(B, L, H, max_kv_len);
     const int slots = QT == 128 ? 512 : 256;         // workgroups resident at once
     const int n_tiles = (max_kv_len + KT - 1) / KT;
@@ -432,16 +440,16 @@ size_t attention_workspace_bytes(int B, int L, int C, int max_kv_len) {
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
     const size_t smem = (size_t)2 * K_TILE_BYTES + 2 * V_TILE_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<4>),
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&]() {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<8>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    });
+    if (attr_err != hipSuccess) return attr_err;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     int max_kv = 0;
     for (int b = 0; b < a.B; ++b) max_kv = a.kv_len[b] > max_kv ? a.kv_len[b] : max_kv;

@@ -64,6 +64,8 @@ struct GemmArgs {
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 // fp32 partial sums the planned launch of an [M, K] x [N, K] product needs (0: its plan does not split k)
 size_t gemm_splitk_floats(int M, int N, int K, int epilogue);
+// Tuning hooks (tests and sweeps): a tile plan that replaces the planner's for every shape; false if not understood.
+bool set_gemm_tile_override(const char* spec);
 
 struct AttnArgs {
     const bf16* q;                    // [B, L, C]
@@ -78,6 +80,8 @@ struct AttnArgs {
     int splits;                       // chosen by attention_plan
 };
 int attention_plan_splits(int B, int L, int H, int max_kv_len);
+// Tuning hooks: waves per workgroup (4, 8; 0 = planner) and key-range splits (0 = planner); -1 leaves a value as is.
+void set_attention_overrides(int waves, int splits);
 size_t attention_workspace_bytes(int B, int L, int C, int max_kv_len);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 
@@ -192,5 +196,11 @@ hipError_t launch_text_relayout(const bf16* k_rows, const bf16* v_rows, bf16* kt
 hipError_t launch_gemv(const float* x, const bf16* w, const float* bias, float* y, int B, int N, int K,
                        int silu_in, hipStream_t s);
 hipError_t launch_timestep_embedding(const float* t_dev, float* emb, int B, int t_dim, double base, hipStream_t s);
+
+// Benchmark-only microkernels: a register-resident loop of bf16 matrix instructions (iters x 8 per wave, eight waves
+// per workgroup) and a streaming copy of `bytes` (multiple of 16) bytes.
+hipError_t launch_peak_mfma(int iters, int workgroups, float* sink, hipStream_t s);
+double peak_mfma_flops(int iters, int workgroups);
+hipError_t launch_peak_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 }  // namespace sdv2

@@ -6,7 +6,8 @@
 // concatenation (its measured extra traffic gamma); here a chunk's keys and values are written once,
 // straight into their ring slots, and nothing is ever moved.
 //
-// All row reductions are one wavefront per row with cross-lane shuffles; no LDS, no atomics.
+// Row reductions use cross-lane shuffles inside a wavefront (RMSNorm, the q/k norm: one wavefront per row;
+// LayerNorm: two wavefronts per row that exchange their partial sums through LDS); no atomics.
 #include "common.h"
 
 namespace sdv2 {

@@ -24,6 +24,7 @@
 //     XCD (measured +100 us on a 64 us launch).
 #include "common.h"
 
+#include <mutex>
 #include <type_traits>
 
 #include <stdio.h>
@@ -359,7 +360,7 @@ __device__ __forceinline__ void load_to_lds_b128(const void* src, void* dst) {
 
 template <int WM, int WN, int TM, int TN, int NS>
 __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n,
-                                                                   int group_m) {
+                                                                   int group_m, int splitk) {
     constexpr int NW = WM * WN;
     constexpr int BK = 64;
     constexpr int BM = 32 * TM * WM;
@@ -381,8 +382,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_dma_kernel(GemmArgs g, i
 
     const int nwg = gridDim.x;                                   // multiple of 8
     const int logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
-    const int t = logical;
-    if (t >= tiles_m * tiles_n) return;
+    const int tiles = tiles_m * tiles_n;
+    if (logical >= tiles * splitk) return;
+    const int ks = logical / tiles;                              // which part of k (0 when k is not split)
+    const int t = logical - ks * tiles;
     const int group_size = group_m * tiles_n;
     const int grp = t / group_size;
     const int first_m = grp * group_m;
@@ -393,9 +396,15 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_dma_kernel(GemmArgs g, i
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
 
-    const int kt0 = 0;
-    const int kt1 = g.K / BK;
+    const int KT = g.K / BK;
+    const int kt0 = (int)((long long)ks * KT / splitk);
+    const int kt1 = (int)((long long)(ks + 1) * KT / splitk);
     const int nk = kt1 - kt0;
+    if (splitk > 1) {                                            // this part's fp32 partial sums, plain stores
+        g.out = g.splitk_partials + (size_t)ks * g.M * g.N;
+        g.epilogue = kEpiPartial;
+        g.bias = nullptr;
+    }
 
     // ---- per-lane source of each of this wave's loads (8-row group wave + NW i of the stacked tile): a 32-bit
     // byte offset into the operand (operands are below 4 GB); the k advance is uniform
@@ -668,13 +677,13 @@ hipError_t launch_ring(const GemmArgs& g, int splitk, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.N + BN - 1) / BN;
     const int grid = (tiles_m * tiles_n * splitk + 7) / 8 * 8;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<WM, WN, TM, TN>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::once_flag attr_once;          // one per instantiation
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&]() {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<WM, WN, TM, TN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    });
+    if (attr_err != hipSuccess) return attr_err;
     // groups of four tile rows: an XCD's 32 concurrent tiles then cover 4 x 8 tiles, the shape with the fewest
     // distinct operand rows per k step
     hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 4, splitk);
@@ -682,24 +691,24 @@ hipError_t launch_ring(const GemmArgs& g, int splitk, hipStream_t s) {
 }
 
 template <int WM, int WN, int TM, int TN, int NS>
-hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
+hipError_t launch_dma(const GemmArgs& g, int splitk, hipStream_t s) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t smem = (size_t)NS * (BM + BN) * 64 * sizeof(bf16);
     static_assert(smem <= 160 * 1024, "LDS stages exceed 160 KB");
     static_assert(smem >= (size_t)WM * WN * EPI_WAVE_FLOATS * sizeof(float), "epilogue staging");
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.N + BN - 1) / BN;
-    const int grid = (tiles_m * tiles_n + 7) / 8 * 8;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, TM, TN, NS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    const int grid = (tiles_m * tiles_n * splitk + 7) / 8 * 8;
+    static std::once_flag attr_once;          // one per instantiation
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&]() {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, TM, TN, NS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    });
+    if (attr_err != hipSuccess) return attr_err;
     const int group_m = (32 * TM * WM >= 256) ? 4 : 8;
     hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, TM, TN, NS>), dim3(grid), dim3(64 * WM * WN), smem, s, g, tiles_m, tiles_n,
-                       group_m);
+                       group_m, splitk);
     return hipGetLastError();
 }
 
@@ -771,13 +780,13 @@ hipError_t launch_one(const GemmArgs& g, int splitk, hipStream_t s) {
     const int grid = (tiles_m * tiles_n * splitk + 7) / 8 * 8;
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
     static_assert((size_t)2 * (BM + BN) * BK * sizeof(bf16) >= 4 * EPI_WAVE_FLOATS * sizeof(float), "epilogue staging");
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TM, TN, BK, PF>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::once_flag attr_once;          // one per instantiation
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&]() {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TM, TN, BK, PF>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    });
+    if (attr_err != hipSuccess) return attr_err;
     const int group_m = 8;
     hipLaunchKernelGGL((gemm_kernel<TM, TN, BK, PF>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m, splitk);
     return hipGetLastError();
@@ -801,40 +810,68 @@ hipError_t launch_tn(const GemmArgs& g, int tn, int splitk, hipStream_t s) {
     return hipErrorInvalidValue;
 }
 
-// Configurations of the direct-load kernel: (waves on M, waves on N, TM, TN, LDS stages).
-constexpr int kDmaConfigs = 6;
+// Configurations of the direct-load kernel: (waves on M, waves on N, TM, TN, LDS stages).  Ids 1-6 are the large
+// tiles for shapes that fill the chip; ids 7 and up are small tiles for the skinny shapes of a single 1024-token
+// chunk, where the tile count has to reach the number of compute units and a k iteration holds only a few matrix
+// instructions per wave: no staging registers and no LDS write instructions, three or four tiles in flight, and
+// two or three workgroups per compute unit to cover the barrier.
+constexpr int kDmaConfigs = 16;
 hipError_t launch_dma_config(const GemmArgs& g, int id, int splitk, hipStream_t s) {
     switch (id) {
-        case 1: return launch_dma<4, 2, 2, 4, 2>(g, s);      // 256 x 256, wave tile 64 x 128
-        case 2: return launch_dma<2, 4, 4, 2, 2>(g, s);      // 256 x 256, wave tile 128 x 64
-        case 3: return launch_dma<2, 4, 2, 2, 3>(g, s);      // 128 x 256
-        case 4: return launch_dma<4, 2, 2, 2, 3>(g, s);      // 256 x 128
+        case 1: return launch_dma<4, 2, 2, 4, 2>(g, splitk, s);      // 256 x 256, wave tile 64 x 128
+        case 2: return launch_dma<2, 4, 4, 2, 2>(g, splitk, s);      // 256 x 256, wave tile 128 x 64
+        case 3: return launch_dma<2, 4, 2, 2, 3>(g, splitk, s);      // 128 x 256
+        case 4: return launch_dma<4, 2, 2, 2, 3>(g, splitk, s);      // 256 x 128
         case 5: return launch_ring<4, 2, 2, 4>(g, splitk, s);        // 256 x 256, ring of four k32 stages
         case 6: return launch_ring<2, 4, 4, 2>(g, splitk, s);
+        case 7: return launch_dma<4, 1, 1, 2, 3>(g, splitk, s);      // 128 x 64, four waves, 72 KB: two workgroups per unit
+        case 8: return launch_dma<4, 1, 1, 2, 4>(g, splitk, s);      // 128 x 64, four stages
+        case 9: return launch_dma<4, 2, 1, 1, 4>(g, splitk, s);      // 128 x 64, eight waves of 32 x 32
+        case 10: return launch_dma<2, 2, 1, 2, 4>(g, splitk, s);     // 64 x 128, four waves
+        case 11: return launch_dma<2, 2, 2, 2, 3>(g, splitk, s);     // 128 x 128, four waves of 64 x 64
+        case 12: return launch_dma<2, 4, 2, 1, 3>(g, splitk, s);     // 128 x 128, eight waves of 64 x 32
+        case 13: return launch_dma<4, 1, 1, 5, 2>(g, splitk, s);     // 128 x 160, four waves, two stages (72 KB)
+        case 14: return launch_dma<4, 1, 1, 5, 3>(g, splitk, s);     // 128 x 160, three stages
+        case 15: return launch_dma<4, 1, 1, 6, 3>(g, splitk, s);     // 128 x 192
+        case 16: return launch_dma<4, 2, 1, 3, 3>(g, splitk, s);     // 128 x 192, eight waves of 32 x 96
     }
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-// Environment override for tuning runs and tests, read at every call: SDV2_GEMM_TILE="tm,tn[,pf[,splitk]]" picks a
-// tile of the register-staged kernel, "d<id>[,splitk]" a configuration of the direct-load kernel (only its ring form,
-// d5 and d6, splits k).
-static bool tile_override(TilePlan* p) {
-    const char* e = getenv("SDV2_GEMM_TILE");
+// Plan override for tuning runs and tests, set through sdv2_tuning_set("gemm_tile", ...): "tm,tn[,pf[,splitk]]"
+// picks a tile of the register-staged kernel, "d<id>[,splitk]" a configuration of the direct-load kernel; an empty
+// string or null clears it.  Not read from the environment: a production
+// process cannot change a kernel plan by accident, and a launch costs no getenv.
+static bool g_have_tile_override = false;
+static TilePlan g_tile_override;
+
+bool set_gemm_tile_override(const char* e) {
+    if (!e || !*e) {
+        g_have_tile_override = false;
+        return true;
+    }
     int a, b, d = 2;
     int dk = 1;
-    if (e && sscanf(e, "d%d,%d", &a, &dk) >= 1 && a >= 1 && a <= kDmaConfigs && dk >= 1 && dk <= 16) {
-        *p = TilePlan{0, 0, 0, a, (a == 5 || a == 6) ? dk : 1};      // only the ring form splits k
+    if (sscanf(e, "d%d,%d", &a, &dk) >= 1 && a >= 1 && a <= kDmaConfigs && dk >= 1 && dk <= 16) {
+        g_tile_override = TilePlan{0, 0, 0, a, dk};
+        g_have_tile_override = true;
         return true;
     }
     int k = 1;
-    if (e && sscanf(e, "%d,%d,%d,%d", &a, &b, &d, &k) >= 2 && a >= 1 && a <= 2 && b >= 2 && b <= 8 &&
+    if (sscanf(e, "%d,%d,%d,%d", &a, &b, &d, &k) >= 2 && a >= 1 && a <= 2 && b >= 2 && b <= 8 &&
         (d == 2 || (d == 3 && b <= 6)) && k >= 1 && k <= 8) {
-        *p = TilePlan{a, b, d, 0, k};
+        g_tile_override = TilePlan{a, b, d, 0, k};
+        g_have_tile_override = true;
         return true;
     }
     return false;
+}
+
+static bool tile_override(TilePlan* p) {
+    if (g_have_tile_override) *p = g_tile_override;
+    return g_have_tile_override;
 }
 
 namespace {
@@ -869,7 +906,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
 
 // Parts of k the plan can really use for this problem and scratch (1: no split).
 static int usable_splitk(const GemmArgs& g, const TilePlan& p) {
-    if ((p.dma && p.dma != 5 && p.dma != 6) || p.splitk <= 1 || g.splitk_partials == nullptr) return 1;
+    if (p.splitk <= 1 || g.splitk_partials == nullptr) return 1;
     int splitk = p.splitk;
     if (splitk > g.K / 128) splitk = g.K / 128;                 // at least two k tiles per part
     if (splitk < 2 || (size_t)splitk * g.M * g.N > g.splitk_floats) return 1;
@@ -893,7 +930,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
 size_t gemm_splitk_floats(int M, int N, int K, int epilogue) {
     TilePlan p = plan_tiles(M, N, K, epilogue);
     tile_override(&p);
-    if ((p.dma && p.dma != 5 && p.dma != 6) || p.splitk <= 1) return 0;
+    if (p.splitk <= 1) return 0;
     return (size_t)p.splitk * M * N;
 }
 

@@ -7,7 +7,6 @@ probabilities to bf16 before the second product.  Bars: 1e-2 of the largest outp
 1e-4 for fp32 outputs; cache bookkeeping and copied cache contents are bit-exact.
 """
 
-import os
 
 import numpy as np
 import pytest
@@ -66,6 +65,17 @@ GEMM_CASES = [
     (260, 256, 2048, 3, "2,8,2,4"),        # four parts, residual
     (1024, 1536, 1536, 1, "1,5,2,3"),      # three parts, GELU in the reduce kernel, ragged N tile
     (130, 384, 192, 0, "1,3,2,8"),         # more parts asked than k allows: clamped to one part per two k tiles
+    (300, 384, 320, 0, "d7"),              # small tiles of the direct-load kernel: 128 x 64, three stages, 5 k tiles
+    (1024, 1536, 1536, 2, "d8"),           # 128 x 64, four stages: the C x C projections of the 1.3B block
+    (200, 640, 192, 1, "d9"),              # 128 x 64 with eight waves of 32 x 32, 3 k tiles in a four-stage ring
+    (260, 512, 448, 3, "d10"),             # 64 x 128
+    (520, 768, 1024, 2, "d11,2"),          # 128 x 128 four waves, two k parts
+    (333, 640, 512, 1, "d12"),             # 128 x 128 eight waves, ragged M and N
+    (1024, 8960, 1536, 1, "d13"),          # 128 x 160 two stages: FFN-1 of the 1.3B block
+    (300, 960, 256, 0, "d14"),             # 128 x 160 three stages
+    (130, 768, 640, 2, "d15,3"),           # 128 x 192, three k parts
+    (1000, 1536, 512, 1, "d16"),           # 128 x 192 with eight waves of 32 x 96
+    (1024, 1536, 8960, 2, "d15,4"),        # FFN-2 of the 1.3B block, four k parts
 ]
 
 
@@ -89,8 +99,7 @@ def test_gemm_matches_oracle(M, N, K, epi, tile):
         want = f64(x0) + gate * acc
     else:
         want = f64(x0) + acc
-    if tile:
-        os.environ["SDV2_GEMM_TILE"] = tile
+    binding.tuning_set("gemm_tile", tile)
     try:
         # with the scratch the plan asks for (NaN-filled: every partial sum that is read was written), then without
         ws_bytes = binding.gemm_workspace_bytes(M, N, K, epi)
@@ -103,7 +112,7 @@ def test_gemm_matches_oracle(M, N, K, epi, tile):
             err = max_rel_err(f64(out), want)
             assert err < (1e-2 if epi < 2 else 1e-4), err
     finally:
-        os.environ.pop("SDV2_GEMM_TILE", None)
+        binding.tuning_set("gemm_tile", None)
 
 
 def test_gemm_full_size_batched_480p_shape_sampled_rows():
@@ -177,17 +186,15 @@ def test_attention_matches_oracle(B, L, H, kv_lens, splits, waves):
         want.append(oracle.attention_dense(f64(q[b]).reshape(L, H, D), f64(k_rows).reshape(n, H, D),
                                            f64(v_rows).reshape(n, H, D)).reshape(L, Cw))
     o = torch.full((B, L, Cw), float("nan"), dtype=torch.bfloat16, device=DEV)
-    if splits:
-        os.environ["SDV2_ATTN_SPLITS"] = str(splits)
-    if waves:
-        os.environ["SDV2_ATTN_WAVES"] = str(waves)
+    binding.tuning_set("attn_splits", splits or None)
+    binding.tuning_set("attn_waves", waves or None)
     try:
         ws = torch.empty(max(binding.attention_workspace_bytes(B, L, Cw, max(kv_lens)), 256), dtype=torch.uint8, device=DEV)
         binding.attention_bf16(q.to(DEV), ks, vts, kv_lens, caps, o, H, ws)
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("SDV2_ATTN_SPLITS", None)
-        os.environ.pop("SDV2_ATTN_WAVES", None)
+        binding.tuning_set("attn_splits", None)
+        binding.tuning_set("attn_waves", None)
     got = f64(o)
     assert np.isfinite(got).all()
     for b in range(B):
