@@ -410,6 +410,22 @@ int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_d
                        int32_t M, int32_t N, int32_t K, int32_t epilogue,
                        const float* gate_a_dev, const float* gate_b_dev, int32_t gate_b_stride,
                        int32_t rows_per_gate, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+/* sdv2_gemm_bf16_noalloc: sdv2_gemm_bf16 for callers that cannot allocate device memory and have no workspace to
+ * hand over (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments,
+ * layouts, epilogues and results as sdv2_gemm_bf16 called with a full workspace; the k-split's fp32 partial sums go
+ * to a scratch array built into the library's device image (sdv2_gemm_noalloc_max_scratch_bytes() = 32 MiB per GPU
+ * that loads the library, held until the process ends).  The call allocates nothing, frees nothing, and does not
+ * synchronise.
+ * Errors: a shape whose planned k-split needs more than that scratch: SDV2_INVALID_ARG (use sdv2_gemm_bf16 with a
+ * workspace); otherwise as sdv2_gemm_bf16.
+ * Every call on one GPU uses that GPU's one scratch array: calls that overlap in time on the same GPU (different
+ * streams) race on it; calls ordered on one stream do not.  Nothing in the scratch has to start at zero: every
+ * partial sum that the reduce pass reads is stored by the same call first. */
+size_t sdv2_gemm_noalloc_max_scratch_bytes(void);
+int32_t sdv2_gemm_bf16_noalloc(const void* a_dev, const void* w_dev, const float* bias_dev, void* out_dev,
+                               int32_t M, int32_t N, int32_t K, int32_t epilogue,
+                               const float* gate_a_dev, const float* gate_b_dev, int32_t gate_b_stride,
+                               int32_t rows_per_gate, void* hip_stream);
 size_t sdv2_attention_workspace_bytes(int32_t B, int32_t L, int32_t C, int32_t max_kv_len);
 int32_t sdv2_attention_bf16(const void* q_dev, const void* const* k_dev, const void* const* vt_dev,
                             const int32_t* kv_len_host, const int32_t* cap_host, void* o_dev,

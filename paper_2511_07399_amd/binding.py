@@ -74,8 +74,8 @@ EXPORTS = (
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
     "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
-    "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_tuning_set",
-    "sdv2_stream_batch_rows_bytes", "sdv2_stream_batch_create", "sdv2_stream_batch_destroy",
+    "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_tuning_set", "sdv2_gemm_noalloc_max_scratch_bytes",
+    "sdv2_gemm_bf16_noalloc", "sdv2_stream_batch_rows_bytes", "sdv2_stream_batch_create", "sdv2_stream_batch_destroy",
     "sdv2_stream_batch_reset", "sdv2_stream_batch_step",
 )
 
@@ -148,6 +148,7 @@ def load_library():
     lib.sdv2_prof_peak_mfma.argtypes = [i32, i32, f32p, sz, C.POINTER(C.c_double), vp]
     lib.sdv2_prof_peak_copy.argtypes = [vp, vp, sz, vp]
     lib.sdv2_tuning_set.argtypes = [C.c_char_p, C.c_char_p]
+    lib.sdv2_gemm_noalloc_max_scratch_bytes.restype = sz
     lib.sdv2_stream_batch_rows_bytes.restype = sz
     lib.sdv2_stream_batch_rows_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
     lib.sdv2_stream_batch_create.argtypes = [C.POINTER(ModelCfg), i32, C.POINTER(i32), i32, f32p, sz, C.POINTER(vp)]
@@ -156,6 +157,7 @@ def load_library():
     lib.sdv2_stream_batch_step.argtypes = [vp, C.POINTER(ModelCfg), C.POINTER(ModelWeights), vp, f32p, i32,
                                            C.POINTER(C.c_float), C.POINTER(vp), C.POINTER(vp), f32p, C.POINTER(i32),
                                            C.POINTER(i32), vp, sz, vp]
+    lib.sdv2_gemm_bf16_noalloc.argtypes = [vp, vp, f32p, vp, i32, i32, i32, i32, f32p, f32p, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -426,6 +428,23 @@ def gemm_bf16(a, w, bias, out, epilogue=0, gate_a=None, gate_b=None, gate_b_stri
     _check(_lib.sdv2_gemm_bf16(_ptr(a), _ptr(w), _ptr(bias), _ptr(out), M, N, K, epilogue, _ptr(gate_a), _ptr(gate_b),
                                gate_b_stride, rows_per_gate, _ptr(workspace),
                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def gemm_noalloc_max_scratch_bytes():
+    load_library()
+    return int(_lib.sdv2_gemm_noalloc_max_scratch_bytes())
+
+
+def gemm_bf16_noalloc(a, w, bias, out, epilogue=0, gate_a=None, gate_b=None, gate_b_stride=0, rows_per_gate=1):
+    load_library()
+    _dev(a, torch.bfloat16)
+    _dev(w, torch.bfloat16)
+    M, K = a.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and tuple(out.shape) == (M, N)
+    _dev(out, torch.bfloat16 if epilogue in (0, 1) else torch.float32)
+    _check(_lib.sdv2_gemm_bf16_noalloc(_ptr(a), _ptr(w), _ptr(bias), _ptr(out), M, N, K, epilogue, _ptr(gate_a),
+                                       _ptr(gate_b), gate_b_stride, rows_per_gate, _stream()))
 
 
 def attention_workspace_bytes(B, L, C_, max_kv_len):

@@ -563,6 +563,56 @@ int32_t sdv2_gemm_bf16(const void* a_dev, const void* w_dev, const float* bias_d
     return SDV2_OK;
 }
 
+// ---- the same product for callers that cannot allocate: the k-split scratch lives in the library's image
+}  // extern "C"
+
+namespace {
+constexpr size_t kNoAllocScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+// One copy per GPU that loads the library, held until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress: the device address differs per GPU and is looked up once per device below.
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+int32_t noalloc_scratch(void** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(SDV2_HIP_ERROR, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (!p) return fail(SDV2_HIP_ERROR, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SDV2_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sdv2_gemm_noalloc_max_scratch_bytes(void) { return kNoAllocScratchBytes; }
+
+int32_t sdv2_gemm_bf16_noalloc(const void* a_dev, const void* w_dev, const float* bias_dev, void* out_dev, int32_t M,
+                               int32_t N, int32_t K, int32_t epilogue, const float* gate_a_dev, const float* gate_b_dev,
+                               int32_t gate_b_stride, int32_t rows_per_gate, void* hip_stream) {
+    if (M <= 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 3) return fail(SDV2_INVALID_ARG, "bad M, N, K or epilogue");
+    const size_t need = gemm_splitk_floats(M, N, K, epilogue) * sizeof(float);
+    if (need > kNoAllocScratchBytes)
+        return fail(SDV2_INVALID_ARG, "this shape's k-split needs %zu bytes of scratch, more than the built-in %zu: use "
+                    "sdv2_gemm_bf16 with a workspace", need, (size_t)kNoAllocScratchBytes);
+    void* ptr = nullptr;
+    if (need) {
+        const int32_t rc = noalloc_scratch(&ptr);
+        if (rc) return rc;
+    }
+    return sdv2_gemm_bf16(a_dev, w_dev, bias_dev, out_dev, M, N, K, epilogue, gate_a_dev, gate_b_dev, gate_b_stride,
+                          rows_per_gate, ptr, need ? kNoAllocScratchBytes : 0, hip_stream);
+}
+
 size_t sdv2_attention_workspace_bytes(int32_t B, int32_t L, int32_t C, int32_t max_kv_len) {
     if (B <= 0 || L <= 0 || C <= 0 || C % SDV2_HEAD_DIM || max_kv_len <= 0) return 0;
     return align_up(attention_workspace_bytes(B, L, C, max_kv_len), 256);
