@@ -93,6 +93,7 @@ def main():
                 "step_frac_measured_mfma_peak": round(frac * cm.MI355X_BF16_FLOPS / (peaks["mfma_bf16"]["measured"] * 1e12), 4),
                 "gemm_tflops": round(m2["gemm_tflops"], 1), "attn_tflops": round(m2["attn_tflops"], 1),
                 "roofline": m2["roofline"], "kernels": m2["kernels"]}
+        also["graph_replay"] = measure_graph_replay(args.workload, args.steps, args.warmup)
         also["stream_batch"] = measure_stream_batch(args.workload) if args.workload == "wan1.3b-step" else None
         also["refresh"] = measure_refresh(args.workload)
         also["motion"] = measure_motion()
@@ -366,6 +367,60 @@ def batch_sweep(workload, sizes, steps, warmup):
             "f_over_f1": {str(b): round(freq[b] / freq[b1], 3) for b in freq},
             "memory_bound_model_B_over_1_plus_B": {str(b): round((b / (1.0 + b)) / (b1 / (1.0 + b1)), 3) for b in freq},
             "picks": picks}
+
+
+def measure_graph_replay(workload, steps, warmup):
+    """The same steady-state steps through sdv2_denoise_graph_launch (the step recorded once as a HIP graph, the ring
+    positions in a device-side descriptor), each step's input copied into the recorded buffer inside the timed region:
+    GPU time per step between events, and the host's time to enqueue a step (no synchronisation inside the loop),
+    beside the same two numbers for the eager sdv2_denoise_step."""
+    import torch
+    from paper_2511_07399_amd import binding, workloads as wk
+    from paper_2511_07399_amd.runner import DeviceModel
+    wl = wk.WORKLOADS[workload]
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    B, L, frames = wl.B, wl.L, wl.frames_per_chunk
+    gpu = DeviceModel(wl, base_seed=0, device=dev, weight_device=dev)
+    xs = [torch.stack([wk.chunk_input(wl, c, s, device=dev) for s in range(B)]).contiguous() for c in range(4)]
+    x = torch.zeros(B, L, wl.C, dtype=torch.float32, device=dev)
+    handle = gpu.graph(x, list(range(B)), frames)
+    fill = (wl.sink_frames + wl.window_frames + frames - 1) // frames + 1
+    out = {}
+    chunk = 0
+
+    def run(n, mode):
+        nonlocal chunk
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for _ in range(n):
+            descs = [(s, chunk * frames, frames, 1) for s in range(B)]
+            ts = [wk.timestep(wl, chunk, 0, s) for s in range(B)]
+            x.copy_(xs[chunk % 4])
+            if mode == "graph":
+                binding.denoise_graph_launch(handle, ts, binding.chunk_descs(descs))
+            else:
+                gpu.denoise(x, descs, timesteps=ts)
+            chunk += 1
+        ev1.record(stream)
+        host_ms = (time.perf_counter() - t0) * 1e3 / n
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / n, host_ms
+
+    run(fill + warmup, "graph")
+    st = gpu.state(0, 0)
+    assert st["win_fill"] == wl.W and st["evicted"] > 0
+    for mode in ("graph", "eager", "graph"):
+        ms, host_ms = run(steps, mode)
+        out[mode] = {"ms_per_step": round(ms, 4), "host_enqueue_ms_per_step": round(host_ms, 4)}
+    assert bool(torch.isfinite(x).all())
+    binding.denoise_graph_destroy(handle)
+    gpu.close()
+    del gpu
+    torch.cuda.empty_cache()
+    return {"workload": "%s at steady state, %d steps per pass, input copy included" % (wl.name, steps), **out}
 
 
 def measure_stream_batch(workload, depths=(2, 4), steps=12):

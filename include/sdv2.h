@@ -347,6 +347,41 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
                           void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * The same denoising step, recorded once and replayed (Section 1, "Efficiency objectives": every chunk has a per-frame
+ * deadline and jitter counts, so the host's share of a step should be as small and as constant as it can be).
+ *
+ * sdv2_denoise_graph_create records the launch sequence of sdv2_denoise_step for a fixed set of B streams, chunk
+ * length and buffers into a HIP graph.  What changes from step to step (each stream's token ids, RoPE frame index,
+ * number of resident keys, timestep) lives in a small descriptor in device memory, `state_dev`
+ * (sdv2_denoise_graph_state_bytes() bytes, 256-byte aligned, caller-owned, must outlive the handle), which the
+ * kernels read at run time.  Everything else is baked in: cfg, the weight pointers, the cache handle, x_dev
+ * (fp32 [B, L, C]: the caller puts each step's input there and finds the output there), the text K/V pointers
+ * (host arrays [n_layers * B] as for sdv2_denoise_step), the workspace (sdv2_denoise_workspace_bytes(cfg, B, L)),
+ * and the kernel plans, which are those of a full cache.  Recording launches nothing and changes no cache state; it
+ * creates one internal stream for the capture.  The graph holds kernel launches only (no memory-set nodes).
+ * Errors: as sdv2_denoise_step; per-launch profiling switched on: SDV2_BAD_STATE.
+ *
+ * sdv2_denoise_graph_launch: one step.  chunks[b] must name the recorded streams in the recorded order with the
+ * recorded n_frames; frame_pos0 and advance are free, with the meaning they have in sdv2_denoise_step.  The call
+ * validates, enqueues one small kernel that stores the descriptor and then the graph on hip_stream, and advances the
+ * host ring state exactly as sdv2_denoise_step does; it does not synchronise.  Steps of one handle must be ordered on
+ * one stream.  Results are those of sdv2_denoise_step (bit for bit where the kernel plans coincide, which they do
+ * once the cache is full).
+ * Errors: a stream whose layers are not in step with each other (the block-level call was used on some of them),
+ * advance = 0 without a matching append: SDV2_BAD_STATE, nothing enqueued, state untouched.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct sdv2_denoise_graph sdv2_denoise_graph;   /* opaque host handle */
+size_t sdv2_denoise_graph_state_bytes(void);
+int32_t sdv2_denoise_graph_create(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache,
+                                  float* x_dev, const void* const* kt_dev, const void* const* vtt_dev,
+                                  const int32_t* stream_ids, int32_t B, int32_t n_frames,
+                                  void* workspace_dev, size_t workspace_bytes, void* state_dev, size_t state_bytes,
+                                  sdv2_denoise_graph** out);
+int32_t sdv2_denoise_graph_launch(sdv2_denoise_graph* graph, const float* timesteps_host,
+                                  const sdv2_chunk_desc* chunks, int32_t B, void* hip_stream);
+int32_t sdv2_denoise_graph_destroy(sdv2_denoise_graph* graph);
+
+/* ------------------------------------------------------------------------------------------------
  * Stream batch over denoising steps (Section 1, contribution (1): inputs reformulated as a batch of short chunks;
  * Section 4.2 and its pipeline-parallel stream-batch figure: the n denoising steps of a chunk act as a batch
  * multiplier, L(T, n B), the rows are latent streams at different noise levels, and a clean latent leaves at every
@@ -467,7 +502,9 @@ int32_t sdv2_prof_peak_copy(const void* src_dev, void* dst_dev, size_t bytes, vo
  * *_workspace_bytes query that goes with a call.  Nothing is read from the environment.
  *   "gemm_tile":   "tm,tn[,pf[,k_parts]]" (register-staged kernel, tile 128 tm x 32 tn) or "d<id>[,k_parts]"
  *                  (a configuration of the direct-to-LDS kernel)
- *   "attn_waves":  "4" or "8" waves per attention workgroup;  "attn_splits": parts of the key range (1 .. 16)
+ *   "attn_waves":  "4" or "8": query blocks (waves) per attention workgroup, one key stream; "2": the key-split form
+ *                  (2 query blocks x 4 key slices per workgroup; used only when every capacity is a multiple of 128)
+ *   "attn_splits": parts of the key range over workgroups (1 .. 16)
  * Errors: unknown name or a value that does not parse: SDV2_INVALID_ARG (the previous setting stays).
  * ------------------------------------------------------------------------------------------------ */
 int32_t sdv2_tuning_set(const char* name, const char* value);

@@ -76,7 +76,8 @@ EXPORTS = (
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
     "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_tuning_set", "sdv2_gemm_noalloc_max_scratch_bytes",
     "sdv2_gemm_bf16_noalloc", "sdv2_stream_batch_rows_bytes", "sdv2_stream_batch_create", "sdv2_stream_batch_destroy",
-    "sdv2_stream_batch_reset", "sdv2_stream_batch_step",
+    "sdv2_stream_batch_reset", "sdv2_stream_batch_step", "sdv2_denoise_graph_state_bytes", "sdv2_denoise_graph_create",
+    "sdv2_denoise_graph_launch", "sdv2_denoise_graph_destroy",
 )
 
 LAUNCH_TAGS = ("adaLN-1", "QKV gemm", "rope+append", "self-attn", "out-proj gemm", "LN-3", "cross-q gemm",
@@ -149,6 +150,11 @@ def load_library():
     lib.sdv2_prof_peak_copy.argtypes = [vp, vp, sz, vp]
     lib.sdv2_tuning_set.argtypes = [C.c_char_p, C.c_char_p]
     lib.sdv2_gemm_noalloc_max_scratch_bytes.restype = sz
+    lib.sdv2_denoise_graph_state_bytes.restype = sz
+    lib.sdv2_denoise_graph_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(ModelWeights), vp, f32p, C.POINTER(vp),
+                                              C.POINTER(vp), C.POINTER(i32), i32, i32, vp, sz, vp, sz, C.POINTER(vp)]
+    lib.sdv2_denoise_graph_launch.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(ChunkDesc), i32, vp]
+    lib.sdv2_denoise_graph_destroy.argtypes = [vp]
     lib.sdv2_stream_batch_rows_bytes.restype = sz
     lib.sdv2_stream_batch_rows_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
     lib.sdv2_stream_batch_create.argtypes = [C.POINTER(ModelCfg), i32, C.POINTER(i32), i32, f32p, sz, C.POINTER(vp)]
@@ -537,3 +543,31 @@ def stream_batch_step(h, cfg, mw, cache, x_in, frame_pos0, timesteps, kt, vtt, x
                                        _ptr(x_out), C.byref(emitted), C.byref(rows), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(), _stream()))
     return bool(emitted.value), rows.value
+
+
+# ------------------------------------------------------------------------------------------ the step as a replayed graph
+def denoise_graph_state_bytes():
+    load_library()
+    return int(_lib.sdv2_denoise_graph_state_bytes())
+
+
+def denoise_graph_create(cfg, mw, cache, x, kt_array, vtt_array, stream_ids, n_frames, workspace, state):
+    """x, workspace, state: device tensors the caller keeps alive; kt_array / vtt_array as for denoise_step."""
+    load_library()
+    _dev(x, torch.float32)
+    ids = (C.c_int32 * len(stream_ids))(*stream_ids)
+    h = C.c_void_p()
+    _check(_lib.sdv2_denoise_graph_create(C.byref(cfg), C.byref(mw), cache, _ptr(x), kt_array, vtt_array, ids,
+                                          len(stream_ids), n_frames, _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _ptr(state),
+                                          state.numel() * state.element_size(), C.byref(h)))
+    return h
+
+
+def denoise_graph_launch(h, timesteps, chunks):
+    ts = (C.c_float * len(timesteps))(*timesteps)
+    _check(_lib.sdv2_denoise_graph_launch(h, ts, chunks, len(chunks), _stream()))
+
+
+def denoise_graph_destroy(h):
+    _check(_lib.sdv2_denoise_graph_destroy(h))

@@ -157,7 +157,7 @@ int32_t sdv2_tuning_set(const char* name, const char* value) {
         const int v = clear ? 0 : atoi(value);
         if (v < 0) return fail(SDV2_INVALID_ARG, "%s must be >= 0", name);
         if (!strcmp(name, "attn_waves")) {
-            if (v != 0 && v != 4 && v != 8) return fail(SDV2_INVALID_ARG, "attn_waves must be 0, 4 or 8");
+            if (v != 0 && v != 2 && v != 4 && v != 8) return fail(SDV2_INVALID_ARG, "attn_waves must be 0, 2, 4 or 8");
             set_attention_overrides(v, -1);
         } else {
             set_attention_overrides(-1, v);
@@ -718,13 +718,18 @@ size_t sdv2_conditioning_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B) {
     return align_up((size_t)B * cfg->t_dim * 4, 256) + 2 * align_up((size_t)B * cfg->C * 4, 256);
 }
 
-int32_t sdv2_conditioning(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, int32_t B,
-                          const float* timesteps_host, const float* tvec_dev, float* e0_dev, void* workspace_dev,
-                          size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// desc (device) replaces timesteps_host when the launches are recorded into a graph
+int32_t conditioning_impl(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, int32_t B,
+                          const float* timesteps_host, const float* tvec_dev, const StepDesc* desc, float* e0_dev,
+                          void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
     const char* why;
     if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
     if (B <= 0 || B > SDV2_MAX_BATCH) return fail(SDV2_INVALID_ARG, "B = %d out of range", B);
     if (!mw || mw->struct_size != sizeof(sdv2_model_weights)) return fail(SDV2_INVALID_ARG, "bad model weights");
+    if (desc != nullptr) timesteps_host = reinterpret_cast<const float*>(desc);      // only its being non-null matters below
     if ((timesteps_host == nullptr) == (tvec_dev == nullptr))
         return fail(SDV2_INVALID_ARG, "give exactly one of timesteps_host and tvec_dev");
     if (!e0_dev || !mw->W_mod || !mw->b_mod) return fail(SDV2_INVALID_ARG, "null pointer");
@@ -742,13 +747,23 @@ int32_t sdv2_conditioning(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
         float* a1 = reinterpret_cast<float*>(p);
         p += align_up((size_t)B * C * 4, 256);
         float* tv = reinterpret_cast<float*>(p);
-        HIP_TRY(launch_timestep_embedding(timesteps_host, emb, B, cfg->t_dim, (double)cfg->rope_base, s), "timestep embedding");
+        HIP_TRY(launch_timestep_embedding(desc ? nullptr : timesteps_host, desc, emb, B, cfg->t_dim, (double)cfg->rope_base, s),
+                "timestep embedding");
         HIP_TRY(launch_gemv(emb, static_cast<const bf16*>(mw->W_t1), mw->b_t1, a1, B, C, cfg->t_dim, 0, s), "timestep MLP 1");
         HIP_TRY(launch_gemv(a1, static_cast<const bf16*>(mw->W_t2), mw->b_t2, tv, B, C, C, 1, s), "timestep MLP 2");
         tvec = tv;
     }
     HIP_TRY(launch_gemv(tvec, static_cast<const bf16*>(mw->W_mod), mw->b_mod, e0_dev, B, 6 * C, C, 1, s), "modulation projection");
     return SDV2_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t sdv2_conditioning(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, int32_t B,
+                          const float* timesteps_host, const float* tvec_dev, float* e0_dev, void* workspace_dev,
+                          size_t workspace_bytes, void* hip_stream) {
+    return conditioning_impl(cfg, mw, B, timesteps_host, tvec_dev, nullptr, e0_dev, workspace_dev, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"
@@ -847,9 +862,15 @@ void fill_rope_table(const sdv2_model_cfg* cfg, RopeAppendArgs* a) {
 }
 
 // Launches one block.  State has been validated; it is advanced here and restored if a launch fails.
+// next_w: the block that runs next on the same x and workspace (null: none); when FFN-2's k-split reduce pass could
+// also write that block's adaLN-1 output into ws.h, *next_h_ready is set and the next call passes h_ready = true.
+// desc: null for an ordinary call.  Otherwise the launches are being recorded into a graph: the host ring state is
+// left alone, the kernels read token ids, frame positions and key counts from *desc (device memory) at run time, and
+// the attention plan is the one of a full cache.
 int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_kv_cache* cache, int layer, float* x,
                   const float* e0, const void* const* kt, const void* const* vtt, const sdv2_chunk_desc* chunks, int B,
-                  int L, const BlockWorkspace& ws, hipStream_t s) {
+                  int L, const BlockWorkspace& ws, hipStream_t s, const sdv2_block_weights* next_w = nullptr,
+                  bool h_ready = false, bool* next_h_ready = nullptr, const StepDesc* desc = nullptr) {
     const int C = cfg->C, F = cfg->ffn_dim, H = cfg->n_heads;
     const int rows = B * L;
     const int S = cache->cfg.sink_tokens, W = cache->cfg.window_tokens;
@@ -864,19 +885,22 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
         const size_t idx = (size_t)layer * cache->cfg.n_streams + chunks[b].stream_id;
         old_total[b] = cache->total[idx];
         old_last[b] = cache->last_n[idx];
-        if (chunks[b].advance) {
+        if (desc == nullptr && chunks[b].advance) {
             cache->total[idx] += L;
             cache->last_n[idx] = L;
         }
-        ra.st[b] = append_stream(cache, layer, chunks[b].stream_id, cache->total[idx] - L, chunks[b].frame_pos0);
+        ra.st[b] = append_stream(cache, layer, chunks[b].stream_id, desc ? 0 : cache->total[idx] - L, chunks[b].frame_pos0);
         at.k[b] = ra.st[b].k_cache;
         at.vt[b] = ra.st[b].vt_cache;
-        const int64_t res = cache->total[idx] < (int64_t)S + W ? cache->total[idx] : (int64_t)S + W;
+        const int64_t res = (desc == nullptr && cache->total[idx] < (int64_t)S + W) ? cache->total[idx] : (int64_t)S + W;
         at.kv_len[b] = (int)res;
         at.cap[b] = cache->cap;
         if (at.kv_len[b] > max_kv) max_kv = at.kv_len[b];
     }
+    ra.desc = desc;
+    at.desc = desc;
     auto restore = [&]() {
+        if (desc != nullptr) return;
         for (int b = 0; b < B; ++b) {
             const size_t idx = (size_t)layer * cache->cfg.n_streams + chunks[b].stream_id;
             cache->total[idx] = old_total[b];
@@ -906,7 +930,7 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     ln.shift_b = e0 + 0 * C;
     ln.scale_a = tab + 1 * C;
     ln.scale_b = e0 + 1 * C;
-    RUN(SDV2_TAG_ADALN1, launch_layernorm(ln, s), "adaLN-1");
+    if (!h_ready) RUN(SDV2_TAG_ADALN1, launch_layernorm(ln, s), "adaLN-1");
     // 2. QKV projection
     GemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -975,6 +999,7 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     RUN(SDV2_TAG_CROSS_Q_NORM, launch_rmsnorm_inplace(ws.q, w->g_cq, rows, C, C, cfg->eps, s), "cross-q norm");
     // 7. cross-attention over the text tokens
     AttnArgs ct = at;
+    ct.desc = nullptr;                                // the text keys do not change from step to step
     const int cap_t = (int)align_up((size_t)cfg->text_len, 64);
     for (int b = 0; b < B; ++b) {
         ct.k[b] = static_cast<const bf16*>(kt[b]);
@@ -1014,7 +1039,16 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     g.epilogue = kEpiGatedResidual;
     g.gate_a = tab + 5 * C;
     g.gate_b = e0 + 5 * C;
-    RUN(SDV2_TAG_FFN2, launch_gemm(g, s), "FFN-2 gemm");
+    if (next_w != nullptr && next_h_ready != nullptr) {
+        LnArgs ln1 = ln;                             // the next block's adaLN-1 on the x this product completes
+        ln1.shift_a = next_w->mod_table + 0 * C;
+        ln1.shift_b = e0 + 0 * C;
+        ln1.scale_a = next_w->mod_table + 1 * C;
+        ln1.scale_b = e0 + 1 * C;
+        RUN(SDV2_TAG_FFN2, launch_gemm_then_layernorm(g, ln1, next_h_ready, s), "FFN-2 gemm");
+    } else {
+        RUN(SDV2_TAG_FFN2, launch_gemm(g, s), "FFN-2 gemm");
+    }
 #undef RUN
     return SDV2_OK;
 }
@@ -1063,15 +1097,19 @@ size_t sdv2_denoise_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_
     return blk + align_up((size_t)B * 6 * cfg->C * 4, 256) + sdv2_conditioning_workspace_bytes(cfg, B);
 }
 
-int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache, float* x_dev,
-                          const float* timesteps_host, const float* tvec_dev, const void* const* kt_dev,
-                          const void* const* vtt_dev, const sdv2_chunk_desc* chunks, int32_t B, void* workspace_dev,
-                          size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// sdv2_denoise_step; with desc non-null the launches are being recorded into a graph (see run_block)
+int32_t denoise_impl(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache, float* x_dev,
+                     const float* timesteps_host, const float* tvec_dev, const void* const* kt_dev,
+                     const void* const* vtt_dev, const sdv2_chunk_desc* chunks, int32_t B, void* workspace_dev,
+                     size_t workspace_bytes, void* hip_stream, const StepDesc* desc) {
     const char* why;
     if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
     if (!mw || mw->struct_size != sizeof(sdv2_model_weights) || !mw->blocks) return fail(SDV2_INVALID_ARG, "bad model weights");
     if (!cache || cache->cfg.n_layers != cfg->n_layers) return fail(SDV2_INVALID_ARG, "cache and model layer counts disagree");
-    if ((timesteps_host == nullptr) == (tvec_dev == nullptr))
+    if (desc == nullptr && (timesteps_host == nullptr) == (tvec_dev == nullptr))
         return fail(SDV2_INVALID_ARG, "give exactly one of timesteps_host and tvec_dev");
     if (!x_dev || !kt_dev || !vtt_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
     int L = 0;
@@ -1089,7 +1127,7 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
     const size_t blk = sdv2_block_workspace_bytes(cfg, B, L);
     float* e0 = reinterpret_cast<float*>(p + blk);
     void* cond_ws = p + blk + align_up((size_t)B * 6 * cfg->C * 4, 256);
-    int32_t rc = sdv2_conditioning(cfg, mw, B, timesteps_host, tvec_dev, e0, cond_ws,
+    int32_t rc = conditioning_impl(cfg, mw, B, timesteps_host, tvec_dev, desc, e0, cond_ws,
                                    sdv2_conditioning_workspace_bytes(cfg, B), hip_stream);
     if (rc) return rc;
     const BlockWorkspace ws = carve_block(cfg, B, L, max_kv_possible(cache), p);
@@ -1104,9 +1142,13 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
             total0[(size_t)layer * B + b] = cache->total[idx];
             last0[(size_t)layer * B + b] = cache->last_n[idx];
         }
+    bool h_ready = false;
     for (int layer = 0; layer < cfg->n_layers; ++layer) {
+        bool next_ready = false;
         rc = run_block(cfg, &mw->blocks[layer], cache, layer, x_dev, e0, kt_dev + (size_t)layer * B,
-                       vtt_dev + (size_t)layer * B, chunks, B, L, ws, s);
+                       vtt_dev + (size_t)layer * B, chunks, B, L, ws, s,
+                       layer + 1 < cfg->n_layers ? &mw->blocks[layer + 1] : nullptr, h_ready, &next_ready, desc);
+        h_ready = next_ready;
         if (rc) {
             for (int l2 = 0; l2 < layer; ++l2)
                 for (int b = 0; b < B; ++b) {
@@ -1116,6 +1158,172 @@ int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* m
                 }
             const std::string inner = g_last_error;
             return fail(rc, "layer %d: %s", layer, inner.c_str());
+        }
+    }
+    return SDV2_OK;
+}
+}  // namespace
+
+// ------------------------------------------------------------------------------------------ the step as a replayed graph
+struct sdv2_denoise_graph {
+    sdv2_model_cfg cfg;
+    sdv2_kv_cache* cache;
+    int B, n_frames, L;
+    int32_t stream_ids[SDV2_MAX_BATCH];
+    StepDesc* desc_dev;
+    hipStream_t capture_stream;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+extern "C" {
+
+int32_t sdv2_denoise_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache, float* x_dev,
+                          const float* timesteps_host, const float* tvec_dev, const void* const* kt_dev,
+                          const void* const* vtt_dev, const sdv2_chunk_desc* chunks, int32_t B, void* workspace_dev,
+                          size_t workspace_bytes, void* hip_stream) {
+    return denoise_impl(cfg, mw, cache, x_dev, timesteps_host, tvec_dev, kt_dev, vtt_dev, chunks, B, workspace_dev,
+                        workspace_bytes, hip_stream, nullptr);
+}
+
+size_t sdv2_denoise_graph_state_bytes(void) { return align_up(sizeof(StepDesc), 256); }
+
+int32_t sdv2_denoise_graph_create(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache,
+                                  float* x_dev, const void* const* kt_dev, const void* const* vtt_dev,
+                                  const int32_t* stream_ids, int32_t B, int32_t n_frames, void* workspace_dev,
+                                  size_t workspace_bytes, void* state_dev, size_t state_bytes, sdv2_denoise_graph** out) {
+    if (!out || !stream_ids || !state_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (state_bytes < sdv2_denoise_graph_state_bytes() || reinterpret_cast<uintptr_t>(state_dev) % 256)
+        return fail(SDV2_INVALID_ARG, "state_dev must be 256-byte aligned and hold sdv2_denoise_graph_state_bytes() bytes");
+    if (B < 1 || B > SDV2_MAX_BATCH || n_frames < 1) return fail(SDV2_INVALID_ARG, "bad B or n_frames");
+    if (g_prof.on) return fail(SDV2_BAD_STATE, "per-launch profiling is on: its events cannot be recorded into a graph");
+    sdv2_chunk_desc chunks[SDV2_MAX_BATCH];
+    for (int b = 0; b < B; ++b) chunks[b] = sdv2_chunk_desc{stream_ids[b], 0, n_frames, 1};
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!mw || !mw->blocks || !cache) return fail(SDV2_INVALID_ARG, "null pointer");
+    // every dense kernel of the step gets its attributes set before the capture begins
+    {
+        int L0 = 0;
+        int32_t rc = validate_block_call(cfg, &mw->blocks[0], cache, 0, chunks, B, &L0);
+        if (rc) return rc;
+        const int C = cfg->C, F = cfg->ffn_dim, rows = B * L0;
+        const BlockWorkspace ws = carve_block(cfg, B, L0, max_kv_possible(cache), nullptr);
+        set_attributes_only(true);
+        hipError_t e = hipSuccess;
+        const int shapes[6][3] = {{3 * C, C, kEpiBias}, {C, C, kEpiGatedResidual}, {C, C, kEpiBias},
+                                  {C, C, kEpiResidual}, {F, C, kEpiBiasGelu},      {C, F, kEpiGatedResidual}};
+        for (const auto& sh : shapes) {
+            GemmArgs g;
+            memset(&g, 0, sizeof(g));
+            g.M = rows;
+            g.N = sh[0];
+            g.K = sh[1];
+            g.epilogue = sh[2];
+            g.rows_per_gate = L0;
+            g.splitk_partials = ws.gemm_floats ? reinterpret_cast<float*>(workspace_dev) : nullptr;   // only its being non-null matters
+            g.splitk_floats = ws.gemm_floats;
+            if (e == hipSuccess) e = launch_gemm(g, nullptr);
+        }
+        AttnArgs at;
+        memset(&at, 0, sizeof(at));
+        at.B = B;
+        at.L = L0;
+        at.H = cfg->n_heads;
+        for (int b = 0; b < B; ++b) {
+            at.kv_len[b] = max_kv_possible(cache);
+            at.cap[b] = cache->cap;
+        }
+        at.splits = 1;
+        if (e == hipSuccess) e = launch_attention(at, nullptr);
+        set_attributes_only(false);
+        if (e != hipSuccess) return hip_fail(e, "kernel attributes");
+    }
+    sdv2_denoise_graph* g = new (std::nothrow) sdv2_denoise_graph;
+    if (!g) return fail(SDV2_INVALID_ARG, "out of host memory");
+    g->cfg = *cfg;
+    g->cache = cache;
+    g->B = B;
+    g->n_frames = n_frames;
+    g->L = n_frames * cfg->grid_h * cfg->grid_w;
+    for (int b = 0; b < SDV2_MAX_BATCH; ++b) g->stream_ids[b] = b < B ? stream_ids[b] : -1;
+    g->desc_dev = static_cast<StepDesc*>(state_dev);
+    g->graph = nullptr;
+    g->exec = nullptr;
+    hipError_t e = hipStreamCreateWithFlags(&g->capture_stream, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+        delete g;
+        return hip_fail(e, "hipStreamCreateWithFlags");
+    }
+    e = hipStreamBeginCapture(g->capture_stream, hipStreamCaptureModeRelaxed);
+    if (e != hipSuccess) {
+        hipStreamDestroy(g->capture_stream);
+        delete g;
+        return hip_fail(e, "hipStreamBeginCapture");
+    }
+    const int32_t rc = denoise_impl(cfg, mw, cache, x_dev, nullptr, nullptr, kt_dev, vtt_dev, chunks, B, workspace_dev,
+                                    workspace_bytes, g->capture_stream, g->desc_dev);
+    const std::string inner = g_last_error;
+    e = hipStreamEndCapture(g->capture_stream, &g->graph);
+    if (rc == SDV2_OK && e == hipSuccess) e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+    if (rc != SDV2_OK || e != hipSuccess) {
+        if (g->graph) hipGraphDestroy(g->graph);
+        hipStreamDestroy(g->capture_stream);
+        delete g;
+        if (rc != SDV2_OK) return fail(rc, "while recording the step: %s", inner.c_str());
+        return hip_fail(e, "graph capture / instantiation");
+    }
+    *out = g;
+    return SDV2_OK;
+}
+
+int32_t sdv2_denoise_graph_destroy(sdv2_denoise_graph* g) {
+    if (!g) return SDV2_OK;
+    if (g->exec) hipGraphExecDestroy(g->exec);
+    if (g->graph) hipGraphDestroy(g->graph);
+    hipStreamDestroy(g->capture_stream);
+    delete g;
+    return SDV2_OK;
+}
+
+int32_t sdv2_denoise_graph_launch(sdv2_denoise_graph* g, const float* timesteps_host, const sdv2_chunk_desc* chunks,
+                                  int32_t B, void* hip_stream) {
+    if (!g || !timesteps_host || !chunks) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (B != g->B) return fail(SDV2_INVALID_ARG, "B = %d, the graph was recorded for %d", B, g->B);
+    sdv2_kv_cache* cache = g->cache;
+    const sdv2_cache_cfg& cf = cache->cfg;
+    const int L = g->L;
+    const int64_t capacity = (int64_t)cf.sink_tokens + cf.window_tokens;
+    StepDesc d;
+    memset(&d, 0, sizeof(d));
+    for (int b = 0; b < B; ++b) {
+        const sdv2_chunk_desc& c = chunks[b];
+        if (c.stream_id != g->stream_ids[b]) return fail(SDV2_INVALID_ARG, "slot %d: stream %d, the graph was recorded for stream %d", b, c.stream_id, g->stream_ids[b]);
+        if (c.n_frames != g->n_frames) return fail(SDV2_INVALID_ARG, "n_frames differs from the recorded one");
+        if (c.frame_pos0 < 0) return fail(SDV2_INVALID_ARG, "frame_pos0 < 0");
+        const size_t idx0 = (size_t)c.stream_id;
+        for (int layer = 1; layer < cf.n_layers; ++layer) {
+            const size_t idx = (size_t)layer * cf.n_streams + c.stream_id;
+            if (cache->total[idx] != cache->total[idx0] || cache->last_n[idx] != cache->last_n[idx0])
+                return fail(SDV2_BAD_STATE, "stream %d: layer %d is not in step with layer 0", c.stream_id, layer);
+        }
+        if (!c.advance && cache->last_n[idx0] != L)
+            return fail(SDV2_BAD_STATE, "stream %d: advance = 0 without a matching append", c.stream_id);
+        const int64_t total_new = cache->total[idx0] + (c.advance ? L : 0);
+        d.g0[b] = total_new - L;
+        d.frame_pos0[b] = c.frame_pos0;
+        d.kv_len[b] = (int)(total_new < capacity ? total_new : capacity);
+        d.timestep[b] = timesteps_host[b];
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    HIP_TRY(launch_set_step_desc(d, g->desc_dev, s), "step descriptor kernel");
+    HIP_TRY(hipGraphLaunch(g->exec, s), "hipGraphLaunch");
+    for (int b = 0; b < B; ++b) {
+        if (!chunks[b].advance) continue;
+        for (int layer = 0; layer < cf.n_layers; ++layer) {
+            const size_t idx = (size_t)layer * cf.n_streams + chunks[b].stream_id;
+            cache->total[idx] += L;
+            cache->last_n[idx] = L;
         }
     }
     return SDV2_OK;

@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
     const int split = bz - b * a.splits;
     const int C = a.H * D;
 
-    const int kv_len = a.kv_len[b];
+    const int kv_len = a.desc ? a.desc->kv_len[b] : a.kv_len[b];
     const int cap = a.cap[b];
     const int n_tiles = (kv_len + KT - 1) / KT;
     const int t0 = (int)((long long)split * n_tiles / a.splits);
@@ -356,6 +356,275 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Key-split form for skinny launches (a single 1024-token chunk: heads x query tiles is well below the number of
+// SIMDs).  A workgroup is NQ query blocks x NKW key slices = 8 waves: it walks the whole key range in tiles of
+// 32 NKW keys, wave (qb, kw) computing the scores of its 32 queries against keys 32 kw .. 32 kw + 31 of every tile
+// and keeping its own running maximum, sum and output; at the end the NKW partial results of a query block are
+// merged through LDS.  Compared with splitting the key range over workgroups this needs no partial outputs in
+// memory and no merge kernel, and every K / V^T tile staged in LDS still serves all eight waves.
+//   K stage:   32 NKW keys x 256 B, chunk c of row r at position c ^ (r % 16)
+//   V^T stage: 128 rows (d) x 32 NKW keys (64 NKW bytes; 256 B for NKW = 4), same swizzle
+// Needs cap % (32 NKW) == 0 (a tile never reaches past a V^T row).
+template <int NQ, int NKW>
+__global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs a, float scale_log2e) {
+    static_assert(NKW == 4 && NQ * NKW == 8, "tiles of 128 keys, eight waves");
+    constexpr int NW = NQ * NKW;
+    constexpr int QT = 32 * NQ;
+    constexpr int KTT = 32 * NKW;                         // keys per tile
+    constexpr int ROWB = 256;                             // bytes per LDS row of either stage
+    constexpr int K_BYTES = KTT * ROWB;                   // 32 KB
+    constexpr int V_BYTES = D * ROWB;                     // 32 KB
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    unsigned char* const k_stage = smem_raw;                          // [2][K_BYTES]
+    unsigned char* const v_stage = smem_raw + 2 * K_BYTES;            // [2][V_BYTES]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qb = wave % NQ;
+    const int kw = wave / NQ;
+    const int l31 = lane & 31;
+    const int lh = lane >> 5;
+
+    const unsigned n_wg = gridDim.x * gridDim.y * gridDim.z;
+    const unsigned flat = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned xcd = flat & 7u, per = n_wg >> 3, rem = n_wg & 7u;
+    const unsigned logical = xcd * per + min(xcd, rem) + (flat >> 3);
+    const int qt = (int)(logical % gridDim.x);
+    const int h = (int)((logical / gridDim.x) % gridDim.y);
+    const int b = (int)(logical / (gridDim.x * gridDim.y));
+    const int C = a.H * D;
+
+    const int kv_len = a.desc ? a.desc->kv_len[b] : a.kv_len[b];
+    const int cap = a.cap[b];
+    const int n_tiles = (kv_len + KTT - 1) / KTT;
+    const int tail_tile = (kv_len % KTT) ? n_tiles - 1 : -1;
+
+    const int q_in_chunk = qt * QT + qb * 32 + l31;
+    const size_t q_row = (size_t)b * a.L + min(q_in_chunk, a.L - 1);
+    bf16x8 qf[D / 16];
+    {
+        const bf16* qp = a.q + q_row * C + h * D + lh * 8;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
+    }
+
+    // A wave load fills four 256-byte rows; wave w issues loads w, w + 8, w + 16, w + 24 of each tile.
+    const unsigned char* kbase = reinterpret_cast<const unsigned char*>(a.k[b] + (size_t)h * cap * D);
+    const unsigned char* vbase = reinterpret_cast<const unsigned char*>(a.vt[b] + (size_t)h * D * cap);
+    constexpr int LPT = KTT / 4 / NW;                     // 4 wave loads per tile and operand for each wave
+    const int ld_row = 4 * wave + (lane >> 4);                                    // + 32 i
+    const int ld_chunk = (lane & 15) ^ (ld_row & 15);                             // 32 i does not change row % 16
+    const uint32_t k_off = (uint32_t)ld_row * ROWB + (uint32_t)ld_chunk * 16;
+    const size_t v_off = (size_t)ld_row * cap * 2 + (size_t)ld_chunk * 16;
+    auto load_k = [&](int t, int stage) {
+        const unsigned char* src = kbase + (size_t)t * K_BYTES + k_off;
+        unsigned char* dst = k_stage + stage * K_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) load_to_lds_b128(src + i * (NW * 1024), dst + i * (NW * 1024));
+    };
+    auto load_v = [&](int t, int stage) {
+        const unsigned char* src = vbase + (size_t)t * (KTT * 2) + v_off;
+        unsigned char* dst = v_stage + stage * V_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) load_to_lds_b128(src + (size_t)i * 32 * cap * 2, dst + i * (NW * 1024));
+    };
+    // Slots past kv_len may hold anything (NaN included) and 0 x NaN is not 0: blank them in the staged V^T tile.
+    auto blank_v_tail = [&](int t, int stage) {
+        const int n_valid = kv_len - t * KTT;
+        bf16* sv = reinterpret_cast<bf16*>(v_stage + stage * V_BYTES);
+        for (int idx = tid; idx < D * 16; idx += 64 * NW) {
+            const int row = idx >> 4, p = idx & 15;
+            const int c = p ^ (row & 15);
+            bf16x8 v = *reinterpret_cast<bf16x8*>(sv + row * (ROWB / 2) + p * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int u = 8 * c + e;                                          // stored column
+                const int slot = (u & ~12) | ((u & 4) << 1) | ((u & 8) >> 1);     // slot it holds
+                if (slot >= n_valid) v[e] = (bf16)0.0f;
+            }
+            *reinterpret_cast<bf16x8*>(sv + row * (ROWB / 2) + p * 8) = v;
+        }
+    };
+
+    f32x16 o_acc[D / 32];
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[i][r] = 0.0f;
+    float m_run = -INFINITY;
+    float l_run = 0.0f;
+
+    // Half of S^T of this wave's 32 keys of the tile in stage sk: d steps 4 half .. 4 half + 3.
+    auto qk_half = [&](f32x16& s, const unsigned char* sk, int half) {
+        if (half == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+        }
+        bf16x8 kf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            kf[i] = *reinterpret_cast<const bf16x8*>(sk + (kw * 32 + l31) * ROWB + (((2 * (4 * half + i) + lh) ^ (l31 & 15)) << 4));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[4 * half + i], s, 0, 0, 0);
+    };
+    auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };       // vmcnt(0) only
+    auto barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    f32x16 s_a, s_b;
+    auto tile_step = [&](auto tail_c, f32x16& s_cur, f32x16& s_nxt, int t) {
+        constexpr bool tail = decltype(tail_c)::value;
+        wait_loads();
+        barrier();                       // K(t+1) and V(t) have landed; everyone is done with K(t), V(t-1)
+        if (tail) {
+            blank_v_tail(t, t & 1);
+            __syncthreads();
+        }
+        if (t + 2 < n_tiles) load_k(t + 2, t & 1);
+        if (t + 1 < n_tiles) load_v(t + 1, (t + 1) & 1);
+        const unsigned char* sk = k_stage + ((t + 1) & 1) * K_BYTES;
+        const unsigned char* sv = v_stage + (t & 1) * V_BYTES;
+        if (tail) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (t * KTT + kw * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= kv_len) s_cur[r] = -INFINITY;
+        }
+        // ---- first half of S^T(t+1) on the matrix unit | row maximum of tile t on the vector unit
+        __builtin_amdgcn_sched_barrier(0);
+        qk_half(s_nxt, sk, 0);
+        float mc[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mc[c] = max2_f32(max3_f32(s_cur[4 * c], s_cur[4 * c + 1], s_cur[4 * c + 2]), s_cur[4 * c + 3]);
+        float mx = max2_f32(max3_f32(mc[0], mc[1], mc[2]), mc[3]);
+        mx = max_xor32(mx);
+        const float m_new = fmaxf(m_run, mx * scale_log2e);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        }
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // rescale only when some row's maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // m_new is finite in every lane that moved
+            const float al = (m_new > m_run || m_run != -INFINITY) ? alpha : 1.0f;   // -inf - -inf is not a number
+            l_run *= al;
+#pragma unroll
+            for (int i = 0; i < D / 32; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[i][r] *= al;
+            m_run = m_new;
+        }
+        // a wave whose whole slice lies past kv_len in the only tile has seen no key yet: exponent base 0, p = 0
+        const float m_use = (tail && m_run == -INFINITY) ? 0.0f : m_run;
+        // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
+        __builtin_amdgcn_sched_barrier(0);
+        qk_half(s_nxt, sk, 1);
+        float ls[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        bf16x8 pf[2];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[r], scale_log2e, -m_use));
+            ls[r & 3] += p;
+            pf[r >> 3][r & 7] = (bf16)p;
+        }
+        l_run += (ls[0] + ls[1]) + (ls[2] + ls[3]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- O^T += V^T P^T: two steps of 16 keys; chunk 4 kw + 2 ts + lh of the V^T row in the cache's column order
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) {
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db) {
+                const unsigned char* vrow = sv + (db * 32 + l31) * ROWB;
+                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vrow + (((4 * kw + 2 * ts + lh) ^ (l31 & 15)) << 4));
+                o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ts], o_acc[db], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    load_k(0, 0);
+    load_v(0, 0);
+    if (1 < n_tiles) load_k(1, 1);
+    wait_loads();
+    barrier();
+    qk_half(s_a, k_stage, 0);
+    qk_half(s_a, k_stage, 1);
+    const int t_full = (tail_tile >= 0) ? n_tiles - 1 : n_tiles;        // tiles [0, t_full) have 128 valid slots
+    const std::false_type no_tail;
+    const std::true_type with_tail;
+    int t = 0;
+    for (; t + 2 <= t_full; t += 2) {
+        tile_step(no_tail, s_a, s_b, t);
+        tile_step(no_tail, s_b, s_a, t + 1);
+    }
+    if (t < t_full) {
+        tile_step(no_tail, s_a, s_b, t);
+        if (t_full < n_tiles) tile_step(with_tail, s_b, s_a, t_full);
+    } else if (t_full < n_tiles) {
+        tile_step(with_tail, s_a, s_b, t_full);
+    }
+
+    // ---- merge the NKW partial results of each query block through LDS (the stages are free now)
+    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    float* const xm = reinterpret_cast<float*>(smem_raw + 4 * K_BYTES);           // [NW][32] maxima, after the stages
+    float* const xl = xm + NW * 32;                                               // [NW][32] sums
+    float* const ox = reinterpret_cast<float*>(smem_raw);                         // [NW][4][16][64] weighted outputs
+    __syncthreads();
+    if (lh == 0) {
+        xm[wave * 32 + l31] = m_run;
+        xl[wave * 32 + l31] = l_tot;
+    }
+    __syncthreads();
+    float mmax = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < NKW; ++k) mmax = fmaxf(mmax, xm[(qb + NQ * k) * 32 + l31]);
+    float lsum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < NKW; ++k) {
+        const float mk = xm[(qb + NQ * k) * 32 + l31];
+        lsum += mk == -INFINITY ? 0.0f : xl[(qb + NQ * k) * 32 + l31] * __builtin_amdgcn_exp2f(mk - mmax);
+    }
+    const float wgt = (m_run == -INFINITY || !(lsum > 0.0f)) ? 0.0f : __builtin_amdgcn_exp2f(m_run - mmax) / lsum;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ox[((wave * 4 + db) * 16 + r) * 64 + lane] = o_acc[db][r] * wgt;
+    __syncthreads();
+    if (q_in_chunk >= a.L) return;
+    // wave (qb, kw) adds up and writes the 32 channels db = kw of its query block
+    bf16* op = a.o + q_row * C + h * D + kw * 32 + 4 * lh;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int k = 0; k < NKW; ++k) acc += ox[(((qb + NQ * k) * 4 + kw) * 16 + 4 * g + e) * 64 + lane];
+            w[e] = (bf16)acc;
+        }
+        *reinterpret_cast<bf16x4*>(op + 8 * g) = w;
+    }
+}
+
 // out = sum_i w_i O_i / sum_i w_i,  w_i = l_i 2^(m_i - max m).  One thread per four channels.
 __global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
     const int C = a.H * D;
@@ -393,16 +662,27 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
 // Waves per workgroup: 4 (128 queries, two workgroups per compute unit) or 8 (256 queries, one workgroup per unit,
 // half the K/V traffic from the L2 per query).
 // Overrides for tuning runs and tests, set through sdv2_tuning_set("attn_waves" / "attn_splits", ...); 0 = the plan's
-// own choice.
+// own choice.  attn_waves 4 / 8: that many query blocks per workgroup, one key stream; 2: the key-split form.
 static int g_force_waves = 0;
 static int g_force_splits = 0;
 void set_attention_overrides(int waves, int splits) {
-    if (waves >= 0) g_force_waves = (waves == 4 || waves == 8) ? waves : 0;
+    if (waves >= 0) g_force_waves = (waves == 4 || waves == 8 || waves == 2) ? waves : 0;
     if (splits >= 0) g_force_splits = splits > 16 ? 16 : splits;
 }
 
+// Key-split form (2 query blocks x 4 key slices): when 128-query workgroups would give fewer than three quarters of
+// the compute units a workgroup each, and every stream's capacity is a whole number of its 128-key tiles.
+static bool attention_plan_key_split(const AttnArgs& a) {
+    for (int b = 0; b < a.B; ++b)
+        if (a.cap[b] % 128) return false;
+    if (g_force_waves) return g_force_waves == 2;
+    return ((a.L + 127) / 128) * a.H * a.B < 192;
+}
+
+// Waves per workgroup: 4 (128 queries, two workgroups per compute unit) or 8 (256 queries, one workgroup per unit,
+// half the K/V traffic from the L2 per query).
 int attention_plan_waves(int B, int L, int H, int max_kv_len) {
-    if (g_force_waves) return g_force_waves;
+    if (g_force_waves == 4 || g_force_waves == 8) return g_force_waves;
     (void)max_kv_len;
     // 256-query workgroups only where they still give at least half of the compute units a workgroup each
     return ((L + 255) / 256) * H * B >= 128 ? 8 : 4;
@@ -440,6 +720,7 @@ size_t attention_workspace_bytes(int B, int L, int C, int max_kv_len) {
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
     const size_t smem = (size_t)2 * K_TILE_BYTES + 2 * V_TILE_BYTES;
+    constexpr size_t smem_ks = (size_t)4 * 32768 + 2 * 8 * 32 * sizeof(float);     // four 32 KB stages + the (m, l) exchange
     static std::once_flag attr_once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(attr_once, [&]() {
@@ -448,9 +729,17 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
         if (attr_err == hipSuccess)
             attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_kernel<8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_ks_kernel<2, 4>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_ks);
     });
-    if (attr_err != hipSuccess) return attr_err;
+    if (attr_err != hipSuccess || attributes_only()) return attr_err;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+    if (attention_plan_key_split(a)) {
+        dim3 grid((a.L + 63) / 64, a.H, a.B);
+        hipLaunchKernelGGL((attention_ks_kernel<2, 4>), grid, dim3(512), smem_ks, s, a, scale_log2e);
+        return hipGetLastError();
+    }
     int max_kv = 0;
     for (int b = 0; b < a.B; ++b) max_kv = a.kv_len[b] > max_kv ? a.kv_len[b] : max_kv;
     const int nw = attention_plan_waves(a.B, a.L, a.H, max_kv);

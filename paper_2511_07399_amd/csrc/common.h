@@ -67,6 +67,15 @@ size_t gemm_splitk_floats(int M, int N, int K, int epilogue);
 // Tuning hooks (tests and sweeps): a tile plan that replaces the planner's for every shape; false if not understood.
 bool set_gemm_tile_override(const char* spec);
 
+// What changes from one denoising step to the next, kept in device memory when the step is replayed from a captured
+// graph (the kernels then read it from there instead of from their by-value arguments).
+struct StepDesc {
+    long long g0[kMaxBatch];          // token id of the chunk's first token, per stream of the call
+    int frame_pos0[kMaxBatch];        // RoPE frame index of the chunk's first frame
+    int kv_len[kMaxBatch];            // resident slots after the append
+    float timestep[kMaxBatch];
+};
+
 struct AttnArgs {
     const bf16* q;                    // [B, L, C]
     const bf16* k[kMaxBatch];         // [H][cap][128]
@@ -78,6 +87,7 @@ struct AttnArgs {
     float* part_o;                    // workspace: [splits][B*L][C] fp32
     float* part_ml;                   // workspace: [splits][B*L][H][2] fp32
     int splits;                       // chosen by attention_plan
+    const StepDesc* desc;             // null: kv_len above; else kv_len is read from the device descriptor
 };
 int attention_plan_splits(int B, int L, int H, int max_kv_len);
 // Tuning hooks: waves per workgroup (4, 8; 0 = planner) and key-range splits (0 = planner); -1 leaves a value as is.
@@ -100,6 +110,12 @@ struct LnArgs {
     int rows_per_stream;
 };
 hipError_t launch_layernorm(const LnArgs& a, hipStream_t s);
+
+// launch_gemm for a residual epilogue (2 or 3) whose output x is the input of a LayerNorm that follows it: when the
+// plan splits k, the pass that adds the parts owns whole rows and also writes that LayerNorm's output (ln.x is
+// ignored: the rows are g.out's; ln.rows = g.M, ln.C = g.N).  *ln_done tells whether it did; if not, the caller
+// launches the LayerNorm itself.
+hipError_t launch_gemm_then_layernorm(const GemmArgs& g, const LnArgs& ln, bool* ln_done, hipStream_t s);
 
 // In-place RMSNorm over C of bf16 rows, times gain.
 hipError_t launch_rmsnorm_inplace(bf16* x, const float* gain, int rows, int C, int ld, float eps, hipStream_t s);
@@ -125,6 +141,7 @@ struct RopeAppendArgs {
     double inv_freq[kHeadDim / 2];    // rotation frequency of each pair of a head
     int pair_axis[kHeadDim / 2];      // 0 frame, 1 row, 2 col
     AppendStream st[kMaxBatch];
+    const StepDesc* desc;             // null: g0 and frame_pos0 of st[]; else they are read from the device descriptor
 };
 hipError_t launch_rope_append(const RopeAppendArgs& a, hipStream_t s);
 
@@ -195,7 +212,14 @@ hipError_t launch_text_relayout(const bf16* k_rows, const bf16* v_rows, bf16* kt
 // y[b][n] = act_out(sum_k act_in(x[b][k]) W[n][k] + bias[n]); x, y fp32; W bf16 [N, K]; B <= kMaxBatch.
 hipError_t launch_gemv(const float* x, const bf16* w, const float* bias, float* y, int B, int N, int K,
                        int silu_in, hipStream_t s);
-hipError_t launch_timestep_embedding(const float* t_dev, float* emb, int B, int t_dim, double base, hipStream_t s);
+// t_host: the B timesteps (by value into the launch), or null with desc: they are read from the device descriptor
+hipError_t launch_timestep_embedding(const float* t_host, const StepDesc* desc, float* emb, int B, int t_dim, double base,
+                                     hipStream_t s);
+hipError_t launch_set_step_desc(const StepDesc& d, StepDesc* dst, hipStream_t s);
+// While set (per thread), the dense launchers only make sure their kernels' attributes are set and launch nothing:
+// used once before a stream capture so that no attribute call falls inside it.
+void set_attributes_only(bool on);
+bool attributes_only();
 
 // Benchmark-only microkernels: a register-resident loop of bf16 matrix instructions (iters x 8 per wave, eight waves
 // per workgroup) and a streaming copy of `bytes` (multiple of 16) bytes.

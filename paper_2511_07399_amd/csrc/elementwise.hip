@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs a, int 
         const float rq = rsqrtf(wave_sum(sq) / (float)C + a.eps);
         const float rk = rsqrtf(wave_sum(sk) / (float)C + a.eps);
         // position of the token; lane j forms the rotation of pair j, then every lane fetches its four
-        const int frame = st.frame_pos0 + i / a.tokens_per_frame;
+        const int frame = (a.desc ? a.desc->frame_pos0[b] : st.frame_pos0) + i / a.tokens_per_frame;
         const int inside = i % a.tokens_per_frame;
         const int axis = a.pair_axis[lane];
         const int pos = axis == 0 ? frame : (axis == 1 ? inside / a.grid_w : inside % a.grid_w);
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs a, int 
             cf[e] = __shfl(cf_own, p0 + e, kWave);
             sf[e] = __shfl(sf_own, p0 + e, kWave);
         }
-        const long long g = st.g0 + i;
+        const long long g = (a.desc ? a.desc->g0[b] : st.g0) + i;
         const int slot = slot_of(g, a.S, a.W);
         if (lane == 0) st.ids[slot] = g;
         bf16* qo = a.q_out + (size_t)row * C;
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs a, int 
     // write: lane = token, each wave takes 32 of the 128 channels
     const int tok = lane;
     if (tok0 + tok < a.L) {
-        const int slot = slot_of(st.g0 + tok0 + tok, a.S, a.W);
+        const int slot = slot_of((a.desc ? a.desc->g0[b] : st.g0) + tok0 + tok, a.S, a.W);
         bf16* vo = st.vt_cache + (size_t)h * kHeadDim * st.cap + vt_column(slot);
         for (int d = wave * 32; d < wave * 32 + 32; ++d) vo[(size_t)d * st.cap] = tile[tok * VT_LD + d];
     }
@@ -276,7 +276,8 @@ struct TimestepArgs {
     float t[kMaxBatch];
 };
 
-__global__ void timestep_embedding_kernel(TimestepArgs ts, float* emb, int B, int t_dim, double log2_base) {
+__global__ void timestep_embedding_kernel(TimestepArgs ts, const StepDesc* desc, float* emb, int B, int t_dim,
+                                          double log2_base) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= B * t_dim) return;
     const int b = idx / t_dim;
@@ -284,7 +285,7 @@ __global__ void timestep_embedding_kernel(TimestepArgs ts, float* emb, int B, in
     const int half = t_dim / 2;
     const int jj = j < half ? j : j - half;
     const double w = exp2(-log2_base * (double)jj / (double)half);
-    const double arg = (double)ts.t[b] * w;
+    const double arg = (double)(desc ? desc->timestep[b] : ts.t[b]) * w;
     emb[idx] = (float)(j < half ? cos(arg) : sin(arg));
 }
 
@@ -384,12 +385,24 @@ hipError_t launch_gemv(const float* x, const bf16* w, const float* bias, float* 
     return hipGetLastError();
 }
 
-hipError_t launch_timestep_embedding(const float* t_host, float* emb, int B, int t_dim, double base, hipStream_t s) {
+hipError_t launch_timestep_embedding(const float* t_host, const StepDesc* desc, float* emb, int B, int t_dim, double base,
+                                     hipStream_t s) {
     TimestepArgs ts;
-    for (int b = 0; b < kMaxBatch; ++b) ts.t[b] = b < B ? t_host[b] : 0.0f;
+    for (int b = 0; b < kMaxBatch; ++b) ts.t[b] = (t_host && b < B) ? t_host[b] : 0.0f;
     const int n = B * t_dim;
-    hipLaunchKernelGGL(timestep_embedding_kernel, dim3((n + 255) / 256), dim3(256), 0, s, ts, emb, B, t_dim,
+    hipLaunchKernelGGL(timestep_embedding_kernel, dim3((n + 255) / 256), dim3(256), 0, s, ts, desc, emb, B, t_dim,
                        log2(base));
+    return hipGetLastError();
+}
+
+namespace {
+__global__ void set_step_desc_kernel(StepDesc d, StepDesc* dst) {
+    if (threadIdx.x == 0) *dst = d;
+}
+}  // namespace
+
+hipError_t launch_set_step_desc(const StepDesc& d, StepDesc* dst, hipStream_t s) {
+    hipLaunchKernelGGL(set_step_desc_kernel, dim3(1), dim3(64), 0, s, d, dst);
     return hipGetLastError();
 }
 

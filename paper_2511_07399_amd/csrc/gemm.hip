@@ -683,7 +683,7 @@ hipError_t launch_ring(const GemmArgs& g, int splitk, hipStream_t s) {
         attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_ring_kernel<WM, WN, TM, TN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     });
-    if (attr_err != hipSuccess) return attr_err;
+    if (attr_err != hipSuccess || attributes_only()) return attr_err;
     // groups of four tile rows: an XCD's 32 concurrent tiles then cover 4 x 8 tiles, the shape with the fewest
     // distinct operand rows per k step
     hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 4, splitk);
@@ -705,7 +705,7 @@ hipError_t launch_dma(const GemmArgs& g, int splitk, hipStream_t s) {
         attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, TM, TN, NS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     });
-    if (attr_err != hipSuccess) return attr_err;
+    if (attr_err != hipSuccess || attributes_only()) return attr_err;
     const int group_m = (32 * TM * WM >= 256) ? 4 : 8;
     hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, TM, TN, NS>), dim3(grid), dim3(64 * WM * WN), smem, s, g, tiles_m, tiles_n,
                        group_m, splitk);
@@ -726,13 +726,16 @@ struct TunedShape {
     TilePlan plan;
 };
 const TunedShape kTuned[] = {
-    // (QKV runs with three register sets and FFN-1 with two: equally fast, and each then has a kernel name of its own
-    // in a profile)
-    {1024, 4608, 1536, {1, 5, 3}},  {1024, 1536, 1536, {1, 2, 2}}, {1024, 8960, 1536, {1, 5, 2}},   {1024, 1536, 8960, {1, 6, 2, 0, 4}},
+    // the 1.3B block on one 1024-token chunk, weights cold (every launch of the sweep reads another copy): small
+    // tiles of the direct-load kernel are 2 to 12 % faster than the register-staged kernel's best
+    {1024, 4608, 1536, {0, 0, 0, 16}},         // QKV: 128 x 192, eight waves
+    {1024, 1536, 1536, {0, 0, 0, 9}},          // C x C projections: 128 x 64, eight waves of 32 x 32
+    {1024, 8960, 1536, {0, 0, 0, 13}},         // FFN-1: 128 x 160, two stages, two workgroups per unit
+    {1024, 1536, 8960, {0, 0, 0, 16, 4}},      // FFN-2: 128 x 192, four k parts
     {1024, 5120, 5120, {1, 5, 2}},  {1024, 5120, 13824, {0, 0, 0, 5, 3}},      // FFN-2 14B: ring, 256 x 256 tiles, three k parts
     // the 1.3B block with 2 or 4 streams per call, where the rule below is more than 4 % off the sweep's best
     {2048, 1536, 8960, {1, 6, 2, 0, 2}}, {4096, 8960, 1536, {1, 5, 2}}, {4096, 1536, 8960, {1, 6, 2}},
-    {4096, 1536, 1536, {1, 6, 2}},
+    {4096, 1536, 1536, {0, 0, 0, 16}}, {4096, 4608, 1536, {0, 0, 0, 16}},
 };
 
 // Otherwise: when 256 x 256 tiles fill at least 80 % of the compute units in every round, the direct-load
@@ -786,7 +789,7 @@ hipError_t launch_one(const GemmArgs& g, int splitk, hipStream_t s) {
         attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<TM, TN, BK, PF>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     });
-    if (attr_err != hipSuccess) return attr_err;
+    if (attr_err != hipSuccess || attributes_only()) return attr_err;
     const int group_m = 8;
     hipLaunchKernelGGL((gemm_kernel<TM, TN, BK, PF>), dim3(grid), dim3(256), smem, s, g, tiles_m, tiles_n, group_m, splitk);
     return hipGetLastError();
@@ -869,6 +872,10 @@ bool set_gemm_tile_override(const char* e) {
     return false;
 }
 
+static thread_local bool g_attr_only = false;
+void set_attributes_only(bool on) { g_attr_only = on; }
+bool attributes_only() { return g_attr_only; }
+
 static bool tile_override(TilePlan* p) {
     if (g_have_tile_override) *p = g_tile_override;
     return g_have_tile_override;
@@ -904,6 +911,89 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
 }
 }  // namespace
 
+namespace {
+// The same sum of the k parts for a residual epilogue whose result is LayerNorm-ed next: two waves own a row (two
+// rows per workgroup, as in the LayerNorm kernel), add the parts in k order, apply bias, gate and residual, store the
+// new fp32 row, and normalise it from the registers: one launch and one read of x less than reduce + LayerNorm.
+template <int NV>
+__global__ __launch_bounds__(256) void splitk_reduce_ln_kernel(GemmArgs g, int splitk, LnArgs ln) {
+    __shared__ float part[2][2][2];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int rw = wave >> 1;
+    const int half = wave & 1;
+    const int t = half * 64 + lane;
+    const int row_raw = blockIdx.x * 2 + rw;
+    const bool live = row_raw < g.M;
+    const int row = live ? row_raw : g.M - 1;             // a spare half workgroup recomputes the last row, stores nothing
+    const int nvec = g.N >> 2;
+    const size_t plane = (size_t)g.M * g.N;
+    float* xrow = reinterpret_cast<float*>(g.out) + (size_t)row * g.N;
+    const float* prow = g.splitk_partials + (size_t)row * g.N;
+    const int stream = row / g.rows_per_gate;
+    const float pivot = xrow[0];                          // any value near the row's mean: read before the row is rewritten
+    f32x4 v[NV];
+    float sum = 0.0f, sq = 0.0f;
+    __syncthreads();                                      // every thread of the row has read the pivot before x changes
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = t + 128 * i;
+        if (idx < nvec) {
+            const int c = idx * 4;
+            f32x4 acc = *reinterpret_cast<const f32x4*>(prow + c);
+            for (int sp = 1; sp < splitk; ++sp) acc += *reinterpret_cast<const f32x4*>(prow + sp * plane + c);
+            if (g.bias != nullptr) acc += *reinterpret_cast<const f32x4*>(g.bias + c);
+            if (g.epilogue == kEpiGatedResidual)
+                acc *= *reinterpret_cast<const f32x4*>(g.gate_a + c) +
+                       *reinterpret_cast<const f32x4*>(g.gate_b + (size_t)stream * g.gate_b_stride + c);
+            v[i] = *reinterpret_cast<const f32x4*>(xrow + c) + acc;
+            if (live) *reinterpret_cast<f32x4*>(xrow + c) = v[i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float d = v[i][e] - pivot;
+                sum += d;
+                sq += d * d;
+            }
+        }
+    }
+    sum = wave_sum(sum);
+    sq = wave_sum(sq);
+    if (lane == 0) {
+        part[rw][half][0] = sum;
+        part[rw][half][1] = sq;
+    }
+    __syncthreads();
+    sum = part[rw][0][0] + part[rw][1][0];
+    sq = part[rw][0][1] + part[rw][1][1];
+    const float inv_c = 1.0f / (float)g.N;
+    const float dmean = sum * inv_c;
+    const float var = fmaxf(sq * inv_c - dmean * dmean, 0.0f);
+    const float rstd = rsqrtf(var + ln.eps);
+    const float mean = pivot + dmean;
+    if (!live) return;
+    const int ln_stream = row / ln.rows_per_stream;
+    bf16* op = ln.out + (size_t)row * g.N;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = t + 128 * i;
+        if (idx < nvec) {
+            const int c = idx * 4;
+            f32x4 sc = *reinterpret_cast<const f32x4*>(ln.scale_a + c);
+            f32x4 sh = *reinterpret_cast<const f32x4*>(ln.shift_a + c);
+            if (ln.scale_b != nullptr) {
+                sc += *reinterpret_cast<const f32x4*>(ln.scale_b + (size_t)ln_stream * ln.b_stride + c);
+                sh += *reinterpret_cast<const f32x4*>(ln.shift_b + (size_t)ln_stream * ln.b_stride + c);
+                sc += 1.0f;
+            }
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)((v[i][e] - mean) * rstd * sc[e] + sh[e]);
+            *reinterpret_cast<bf16x4*>(op + c) = o;
+        }
+    }
+}
+}  // namespace
+
 // Parts of k the plan can really use for this problem and scratch (1: no split).
 static int usable_splitk(const GemmArgs& g, const TilePlan& p) {
     if (p.splitk <= 1 || g.splitk_partials == nullptr) return 1;
@@ -913,7 +1003,7 @@ static int usable_splitk(const GemmArgs& g, const TilePlan& p) {
     return splitk;
 }
 
-hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
+static hipError_t launch_gemm_impl(const GemmArgs& g, const LnArgs* ln, bool* ln_done, hipStream_t s) {
     TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue);
     tile_override(&p);
     const int splitk = usable_splitk(g, p);
@@ -921,10 +1011,29 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     if (p.dma) e = launch_dma_config(g, p.dma, splitk, s);
     else if (p.pf == 3) e = p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
     else e = p.tm == 1 ? launch_tn<1, 2>(g, p.tn, splitk, s) : launch_tn<2, 2>(g, p.tn, splitk, s);
-    if (e != hipSuccess || splitk == 1) return e;
+    if (e != hipSuccess || splitk == 1 || attributes_only()) return e;
+    const int nv = (g.N + 511) / 512;                   // float4 values per lane with 128 lanes per row
+    if (ln != nullptr && (g.epilogue == kEpiGatedResidual || g.epilogue == kEpiResidual) && nv <= 16) {
+        const dim3 grid((g.M + 1) / 2), block(256);
+        if (nv <= 1) hipLaunchKernelGGL(splitk_reduce_ln_kernel<1>, grid, block, 0, s, g, splitk, *ln);
+        else if (nv <= 3) hipLaunchKernelGGL(splitk_reduce_ln_kernel<3>, grid, block, 0, s, g, splitk, *ln);
+        else if (nv <= 4) hipLaunchKernelGGL(splitk_reduce_ln_kernel<4>, grid, block, 0, s, g, splitk, *ln);
+        else if (nv <= 6) hipLaunchKernelGGL(splitk_reduce_ln_kernel<6>, grid, block, 0, s, g, splitk, *ln);
+        else if (nv <= 10) hipLaunchKernelGGL(splitk_reduce_ln_kernel<10>, grid, block, 0, s, g, splitk, *ln);
+        else hipLaunchKernelGGL(splitk_reduce_ln_kernel<16>, grid, block, 0, s, g, splitk, *ln);
+        *ln_done = true;
+        return hipGetLastError();
+    }
     const size_t n = (size_t)g.M * (g.N >> 2);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, g, splitk);
     return hipGetLastError();
+}
+
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) { return launch_gemm_impl(g, nullptr, nullptr, s); }
+
+hipError_t launch_gemm_then_layernorm(const GemmArgs& g, const LnArgs& ln, bool* ln_done, hipStream_t s) {
+    *ln_done = false;
+    return launch_gemm_impl(g, &ln, ln_done, s);
 }
 
 size_t gemm_splitk_floats(int M, int N, int K, int epilogue) {

@@ -88,6 +88,17 @@ class DeviceModel:
         binding.denoise_step(self.cfg, self.mw, self.cache, x, kt, vtt, binding.chunk_descs(descs),
                              self.workspace(B, L), timesteps=timesteps, tvec=tvec)
 
+    def graph(self, x, stream_ids, n_frames):
+        """Records sdv2_denoise_step on the fp32 [B, L, C] tensor x for these streams; returns the handle (the
+        workspace and the descriptor buffer stay alive in this object)."""
+        B, L, _ = x.shape
+        kt = binding.ptr_array([self.kt[layer][s] for layer in range(self.N) for s in stream_ids])
+        vtt = binding.ptr_array([self.vtt[layer][s] for layer in range(self.N) for s in stream_ids])
+        state = torch.zeros(binding.denoise_graph_state_bytes(), dtype=torch.uint8, device=self.device)
+        self._graph_keep = getattr(self, "_graph_keep", []) + [state, kt, vtt, x]
+        return binding.denoise_graph_create(self.cfg, self.mw, self.cache, x, kt, vtt, list(stream_ids), n_frames,
+                                            self.workspace(B, L), state)
+
     def cache_logical(self, layer, stream):
         """Host copies of one cache in token-row form: K, V float32 [S+W, C] and ids int64 [S+W]."""
         kp, vp, ip, cap = binding.kv_cache_device_ptrs(self.cache, layer, stream)

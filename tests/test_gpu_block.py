@@ -254,8 +254,11 @@ def test_wan14b_step_layers_0_19_39_fed_the_gpu_layer_input():
     picked = (0, 19, 39)
     dev = "cuda:0"
     gpu = GpuRunner(wl, n_streams=1, weight_device=lambda layer: "cpu" if layer in picked else dev)
-    vis = visible_branches(wl)
     for target in picked:
+        # at depth the rows of the hidden state share a large common part (the seeded model adds about one per layer),
+        # the values a query averages no longer cancel and the self-attention branch is about eight times larger than
+        # in block 0: a smaller gate 1 keeps the three branches comparable there
+        vis = visible_branches(wl) if target == 0 else visible_branches(wl, g1=0.5)
         plain = {k: gpu.layers[target][k].clone() for k in ("mod_table", "W_co", "b_co")}
         vis(gpu.layers[target], target)                       # in place: the C structs keep pointing at these tensors
         ora = OracleRunner(wl, n_streams=1, layer_ids=(target,), edit=vis)
@@ -267,19 +270,25 @@ def test_wan14b_step_layers_0_19_39_fed_the_gpu_layer_input():
             assert max_rel_err(e0g[0].cpu().numpy(), e0o) <= 1e-3
             xg = wk.chunk_input(wl, chunk).to(dev).reshape(1, wl.L, wl.C).contiguous()
             desc = (0, chunk, 1, 1)
+            # the compared block takes the same modulation with its two gate rows zeroed, so that its gates are the
+            # edited table's: with this model's seeded conditioning e0 moves the gates by up to 0.5 and the hidden state
+            # grows by about one per layer, and the FFN branch would be fifteen times the self-attention branch at depth
+            e0g_t, e0o_t = e0g.clone(), e0o.copy()
+            e0g_t[:, (2, 5)] = 0.0
+            e0o_t[[2, 5]] = 0.0
             for layer in range(wl.N):
                 x_in = xg[0].cpu().double().numpy() if layer == target else None
-                gpu.block(layer, xg, e0g, [desc])
+                gpu.block(layer, xg, e0g_t if layer == target else e0g, [desc])
                 if layer != target:
                     continue
                 dbg = {}
-                xo = ora.block(layer, x_in, e0o, desc, debug=dbg)
+                xo = ora.block(layer, x_in, e0o_t, desc, debug=dbg)
                 upd_o = xo - x_in
                 err = max_rel_err(xg[0].cpu().double().numpy() - x_in, upd_o)
                 floor = branch_floor(dbg)
                 print("layer %d chunk %d: update err %.3e, max |x_in| %.1f, max |update| %.2f, smallest branch %.2f"
                       % (layer, chunk, err, np.abs(x_in).max(), np.abs(upd_o).max(), floor), flush=True)
-                assert floor >= 5 * TOL_X * np.abs(xo).max(), (chunk, layer, floor)
+                assert floor >= 5 * TOL_X * np.abs(upd_o).max(), (chunk, layer, floor)
                 assert err <= TOL_X, (chunk, layer, err)
                 assert gpu.state(layer, 0) == ora.caches[layer][0].state()
                 assert np.array_equal(gpu.slot_map(layer, 0), ora.caches[layer][0].slot_map())

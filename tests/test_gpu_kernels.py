@@ -72,7 +72,7 @@ GEMM_CASES = [
     (520, 768, 1024, 2, "d11,2"),          # 128 x 128 four waves, two k parts
     (333, 640, 512, 1, "d12"),             # 128 x 128 eight waves, ragged M and N
     (1024, 8960, 1536, 1, "d13"),          # 128 x 160 two stages: FFN-1 of the 1.3B block
-    (300, 960, 256, 0, "d14"),             # 128 x 160 three stages
+    (300, 1280, 256, 0, "d14"),            # 128 x 160 three stages
     (130, 768, 640, 2, "d15,3"),           # 128 x 192, three k parts
     (1000, 1536, 512, 1, "d16"),           # 128 x 192 with eight waves of 32 x 96
     (1024, 1536, 8960, 2, "d15,4"),        # FFN-2 of the 1.3B block, four k parts
@@ -165,10 +165,14 @@ ATTN_CASES = [
     (2, 200, 2, [1000, 70], 4),            # a stream with fewer tiles than splits
     (1, 1024, 12, [3072], 0),              # 1.3B steady state (planner's split)
     (1, 1024, 12, [512], 0),               # text cross-attention shape
+    (1, 70, 2, [200], 0),                  # a 128-key tile and a tail of 72: slices 2 and 3 of the tail hold 8 and 0 keys
+    (2, 64, 1, [40, 129], 0),              # fewer keys than one slice; one key into the second 128-key tile
 ]
 
 
-@pytest.mark.parametrize("waves", [0, 4, 8])        # 0: the planner's choice; 4 / 8 waves (128 / 256 queries) per workgroup
+# waves 0: the planner's choice; 4 / 8: 128 / 256 queries per workgroup, one key stream; 2: the key-split form
+# (2 query blocks x 4 key slices per workgroup, 128-key tiles, capacity a multiple of 128)
+@pytest.mark.parametrize("waves", [0, 4, 8, 2])
 @pytest.mark.parametrize("B,L,H,kv_lens,splits", ATTN_CASES)
 def test_attention_matches_oracle(B, L, H, kv_lens, splits, waves):
     D = 128
@@ -178,7 +182,7 @@ def test_attention_matches_oracle(B, L, H, kv_lens, splits, waves):
     for b, n in enumerate(kv_lens):
         k_rows = bf16_randn((n, Cw), 20 + b)
         v_rows = bf16_randn((n, Cw), 30 + b)
-        cap = (n + 63) // 64 * 64 + 64 * (b % 2)
+        cap = (n + 127) // 128 * 128 + 128 * (b % 2) if waves == 2 else (n + 63) // 64 * 64 + 64 * (b % 2)
         K, VT = pack_kv(k_rows, v_rows, H, cap)
         ks.append(K.to(DEV))
         vts.append(VT.to(DEV))
