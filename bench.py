@@ -264,27 +264,39 @@ def measure(workload, steps, warmup, copy_calibration, n_dist=0):
     sum_us = lambda tags: sum(float(np.mean(per_tag[t])) * 1e3 for t in tags if t in per_tag)
     gemm_tflops = sum(flops[t] for t in gemm_tags) / (sum_us(gemm_tags) * 1e-6) / 1e12
     attn_tflops = sum(flops[t] for t in attn_tags) / (sum_us(attn_tags) * 1e-6) / 1e12
-    # Dominant kernel = the group of launch sites that run the same kernel on the same shape and take the largest
-    # share of the step (the three C x C projections are one group: same kernel, same M, N, K).
-    groups = {
-        "C x C projection GEMM (out-proj, cross-q, cross-out; M=%d, N=%d, K=%d, bf16)" % (rows, Cw, Cw): (4, 6, 9),
-        "QKV GEMM (M=%d, N=%d, K=%d, bf16)" % (rows, 3 * Cw, Cw): (1,),
-        "FFN-1 GEMM (M=%d, N=%d, K=%d, bf16, GELU epilogue)" % (rows, wl.F, Cw): (11,),
-        "FFN-2 GEMM (M=%d, N=%d, K=%d, bf16, gated residual)" % (rows, Cw, wl.F): (12,),
-        "self-attention over the rolling cache (%d queries x %d keys x %d heads, bf16)" % (rows, l_kv, wl.H): (3,),
-        "text cross-attention (%d queries x %d keys x %d heads, bf16)" % (rows, wl.L_t, wl.H): (8,),
+    # Dominant kernel = the kernel instantiation (as a profiler names it) whose launch sites together take the largest
+    # share of the step: the library tells which instantiation its planner picks for each site's shape.
+    cap = (wl.S + wl.W + 63) // 64 * 64
+    cap_t = (wl.L_t + 63) // 64 * 64
+    site_kernel = {
+        1: binding.prof_kernel_name("gemm", B, L, 3 * Cw, Cw, 0), 4: binding.prof_kernel_name("gemm", B, L, Cw, Cw, 2),
+        6: binding.prof_kernel_name("gemm", B, L, Cw, Cw, 0), 9: binding.prof_kernel_name("gemm", B, L, Cw, Cw, 3),
+        11: binding.prof_kernel_name("gemm", B, L, wl.F, Cw, 1), 12: binding.prof_kernel_name("gemm", B, L, Cw, wl.F, 2),
+        3: binding.prof_kernel_name("attention", B, L, wl.H, l_kv, cap),
+        8: binding.prof_kernel_name("attention", B, L, wl.H, wl.L_t, cap_t),
     }
+    groups = {}
+    for tag, name in site_kernel.items():
+        if tag in per_tag:
+            groups.setdefault(name, []).append(tag)
     all_us = sum_us(per_tag.keys())
     dom_name, dom_tags = max(groups.items(), key=lambda kv: sum_us(kv[1]))
-    dom_us = sum_us(dom_tags) / len(dom_tags)                       # average duration of one launch of the group
-    dom_flops = flops[dom_tags[0]]
+    dom_tags = sorted(dom_tags)
+    dom_us = sum_us(dom_tags) / len(dom_tags)                       # average duration of one launch site of the kernel
+    dom_flops = sum(flops[t] for t in dom_tags) / len(dom_tags)     # average algorithmic flops of one such launch site
     achieved = dom_flops / (dom_us * 1e-6) / 1e12
+    for tag, name in site_kernel.items():
+        if binding.LAUNCH_TAGS[tag] in kernels:
+            kernels[binding.LAUNCH_TAGS[tag]]["kernel"] = name
     roofline = {
         "bound": "mfma", "kernel": dom_name, "launch_sites": [binding.LAUNCH_TAGS[t] for t in dom_tags],
         "share_of_step_time": round(sum_us(dom_tags) / all_us, 4),
         "achieved": round(achieved, 1), "peak": cm.MI355X_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
         "frac": round(achieved * 1e12 / cm.MI355X_BF16_FLOPS, 4), "avg_launch_us": round(dom_us, 2),
-        "flops_per_launch": dom_flops, "traffic": load_traffic(wl.name, dom_name.split(" (")[0]),
+        "flops_per_launch": dom_flops,
+        "note": "durations are HIP-event brackets around each launch (the reduce pass of a k-split GEMM and the merge "
+                "pass of a split-KV attention are launches of their own); they read 2-3 us above rocprofv3's kernel durations",
+        "traffic": load_traffic(wl.name, dom_name),
     }
     step_flops = wl.N * cm.block_flops(rows, Cw, wl.F, l_kv, wl.L_t)
     latency = None
@@ -563,14 +575,14 @@ def measure_motion(reps=20):
     return out
 
 
-def load_traffic(workload, launch_site):
+def load_traffic(workload, kernel):
     """HBM bytes per launch of the dominant kernel, as derived from the rocprofv3 --pmc runs whose summary
     is committed under profiles/ (null when no such measurement is recorded for this kernel of this workload:
     counters cannot be read from inside the timed run)."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get(launch_site)
+            return json.load(f).get(workload, {}).get(kernel)
     except (OSError, ValueError):
         return None
 

@@ -478,7 +478,11 @@ enum sdv2_launch_tag {
     SDV2_TAG_ADALN1 = 0, SDV2_TAG_QKV = 1, SDV2_TAG_ROPE_APPEND = 2, SDV2_TAG_SELF_ATTN = 3,
     SDV2_TAG_OUT_PROJ = 4, SDV2_TAG_LN3 = 5, SDV2_TAG_CROSS_Q = 6, SDV2_TAG_CROSS_Q_NORM = 7,
     SDV2_TAG_CROSS_ATTN = 8, SDV2_TAG_CROSS_OUT = 9, SDV2_TAG_ADALN2 = 10, SDV2_TAG_FFN1 = 11,
-    SDV2_TAG_FFN2 = 12, SDV2_TAG_COUNT = 13
+    SDV2_TAG_FFN2 = 12,
+    SDV2_TAG_GEMM_REDUCE = 13,    /* second pass of a product whose k range was split: sum of the parts + epilogue
+                                     (+ the next LayerNorm when it is fused in) */
+    SDV2_TAG_ATTN_MERGE = 14,     /* second pass of an attention whose key range was split over workgroups */
+    SDV2_TAG_COUNT = 15
 };
 int32_t sdv2_prof_begin(int32_t max_samples);
 int32_t sdv2_prof_end(int32_t* tags_out, float* ms_out, int32_t capacity, int32_t* n_out);
@@ -492,6 +496,12 @@ int32_t sdv2_prof_end(int32_t* tags_out, float* ms_out, int32_t capacity, int32_
  *   through HBM when the buffers exceed the caches.
  * Both only enqueue one kernel; the caller times it with events on the same stream.
  * ------------------------------------------------------------------------------------------------ */
+/* sdv2_prof_kernel_name: the kernel instantiation the library's planner picks, spelled as a profiler prints it, so
+ * that the benchmark can group launch sites by kernel the way a rocprofv3 summary does.
+ *   kind 0: the GEMM of B * L rows with N = a0, K = a1, epilogue a2;  kind 1: attention of B streams x L queries,
+ *   a0 heads, a1 keys, cache capacity a2 slots.  Host only; `out` receives a NUL-terminated string. */
+int32_t sdv2_prof_kernel_name(int32_t kind, int32_t B, int32_t L, int32_t a0, int32_t a1, int32_t a2, char* out,
+                              size_t capacity);
 int32_t sdv2_prof_peak_mfma(int32_t iters, int32_t workgroups, float* sink_dev, size_t sink_floats, double* flops_out,
                             void* hip_stream);
 int32_t sdv2_prof_peak_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);

@@ -74,14 +74,15 @@ EXPORTS = (
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
     "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
-    "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_tuning_set", "sdv2_gemm_noalloc_max_scratch_bytes",
+    "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_prof_kernel_name", "sdv2_tuning_set", "sdv2_gemm_noalloc_max_scratch_bytes",
     "sdv2_gemm_bf16_noalloc", "sdv2_stream_batch_rows_bytes", "sdv2_stream_batch_create", "sdv2_stream_batch_destroy",
     "sdv2_stream_batch_reset", "sdv2_stream_batch_step", "sdv2_denoise_graph_state_bytes", "sdv2_denoise_graph_create",
     "sdv2_denoise_graph_launch", "sdv2_denoise_graph_destroy",
 )
 
 LAUNCH_TAGS = ("adaLN-1", "QKV gemm", "rope+append", "self-attn", "out-proj gemm", "LN-3", "cross-q gemm",
-               "cross-q norm", "cross-attn", "cross-out gemm", "adaLN-2", "FFN-1 gemm", "FFN-2 gemm")
+               "cross-q norm", "cross-attn", "cross-out gemm", "adaLN-2", "FFN-1 gemm", "FFN-2 gemm", "k-split reduce",
+               "split-KV merge")
 
 _lib = None
 
@@ -149,6 +150,7 @@ def load_library():
     lib.sdv2_prof_peak_mfma.argtypes = [i32, i32, f32p, sz, C.POINTER(C.c_double), vp]
     lib.sdv2_prof_peak_copy.argtypes = [vp, vp, sz, vp]
     lib.sdv2_tuning_set.argtypes = [C.c_char_p, C.c_char_p]
+    lib.sdv2_prof_kernel_name.argtypes = [i32, i32, i32, i32, i32, i32, C.c_char_p, sz]
     lib.sdv2_gemm_noalloc_max_scratch_bytes.restype = sz
     lib.sdv2_denoise_graph_state_bytes.restype = sz
     lib.sdv2_denoise_graph_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(ModelWeights), vp, f32p, C.POINTER(vp),
@@ -500,6 +502,14 @@ def prof_peak_copy(src, dst):
     assert dst.numel() * dst.element_size() == n
     _check(_lib.sdv2_prof_peak_copy(_ptr(src), _ptr(dst), n, _stream()))
     return n
+
+
+def prof_kernel_name(kind, B, L, a0, a1, a2):
+    """kind "gemm": (N, K, epilogue) = (a0, a1, a2); kind "attention": (heads, keys, capacity) = (a0, a1, a2)."""
+    load_library()
+    buf = C.create_string_buffer(128)
+    _check(_lib.sdv2_prof_kernel_name(0 if kind == "gemm" else 1, B, L, a0, a1, a2, buf, 128))
+    return buf.value.decode()
 
 
 def tuning_set(name, value=None):

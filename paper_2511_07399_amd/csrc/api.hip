@@ -916,6 +916,19 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
         }                                                                 \
     } while (0)
 
+    // a product on the matrix cores and its second pass (the sum of the k parts; the merge of a split key range) are
+    // timed as two launches
+#define RUN_GEMM(tag, what)                                                         \
+    do {                                                                            \
+        RUN(tag, launch_gemm_part(g, s, 1), what);                                  \
+        if (gemm_splits_k(g)) RUN(SDV2_TAG_GEMM_REDUCE, launch_gemm_part(g, s, 2), what " (sum of the k parts)"); \
+    } while (0)
+#define RUN_ATTN(tag, args, what)                                                   \
+    do {                                                                            \
+        RUN(tag, launch_attention(args, s, 1), what);                               \
+        if (attention_has_merge_pass(args)) RUN(SDV2_TAG_ATTN_MERGE, launch_attention(args, s, 2), what " (merge)"); \
+    } while (0)
+
     const float* tab = w->mod_table;
     LnArgs ln;
     ln.x = x;
@@ -946,7 +959,7 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     g.N = 3 * C;
     g.K = C;
     g.epilogue = kEpiBias;
-    RUN(SDV2_TAG_QKV, launch_gemm(g, s), "QKV gemm");
+    RUN_GEMM(SDV2_TAG_QKV, "QKV gemm");
     // 3. q/k RMSNorm + RoPE + append into the ring
     ra.qkv = ws.qkv;
     ra.q_out = ws.q;
@@ -972,7 +985,7 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     at.splits = attention_plan_splits(B, L, H, max_kv);
     at.part_o = ws.attn;
     at.part_ml = ws.attn + (size_t)at.splits * rows * C;
-    RUN(SDV2_TAG_SELF_ATTN, launch_attention(at, s), "self-attention");
+    RUN_ATTN(SDV2_TAG_SELF_ATTN, at, "self-attention");
     // 5. output projection, gated residual
     g.a = ws.o;
     g.w = static_cast<const bf16*>(w->W_o);
@@ -983,7 +996,7 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     g.epilogue = kEpiGatedResidual;
     g.gate_a = tab + 2 * C;
     g.gate_b = e0 + 2 * C;
-    RUN(SDV2_TAG_OUT_PROJ, launch_gemm(g, s), "out-proj gemm");
+    RUN_GEMM(SDV2_TAG_OUT_PROJ, "out-proj gemm");
     // 6. LayerNorm-3 (affine) and the cross-attention query
     ln.scale_a = w->ln3_gamma;
     ln.scale_b = nullptr;
@@ -995,7 +1008,7 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     g.bias = w->b_cq;
     g.out = ws.q;
     g.epilogue = kEpiBias;
-    RUN(SDV2_TAG_CROSS_Q, launch_gemm(g, s), "cross-q gemm");
+    RUN_GEMM(SDV2_TAG_CROSS_Q, "cross-q gemm");
     RUN(SDV2_TAG_CROSS_Q_NORM, launch_rmsnorm_inplace(ws.q, w->g_cq, rows, C, C, cfg->eps, s), "cross-q norm");
     // 7. cross-attention over the text tokens
     AttnArgs ct = at;
@@ -1009,13 +1022,13 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     }
     ct.splits = attention_plan_splits(B, L, H, cfg->text_len);
     ct.part_ml = ws.attn + (size_t)ct.splits * rows * C;
-    RUN(SDV2_TAG_CROSS_ATTN, launch_attention(ct, s), "cross-attention");
+    RUN_ATTN(SDV2_TAG_CROSS_ATTN, ct, "cross-attention");
     g.a = ws.o;
     g.w = static_cast<const bf16*>(w->W_co);
     g.bias = w->b_co;
     g.out = x;
     g.epilogue = kEpiResidual;
-    RUN(SDV2_TAG_CROSS_OUT, launch_gemm(g, s), "cross-out gemm");
+    RUN_GEMM(SDV2_TAG_CROSS_OUT, "cross-out gemm");
     // 8. adaLN-2 and the FFN
     ln.shift_a = tab + 3 * C;
     ln.shift_b = e0 + 3 * C;
@@ -1029,7 +1042,7 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
     g.N = F;
     g.K = C;
     g.epilogue = kEpiBiasGelu;
-    RUN(SDV2_TAG_FFN1, launch_gemm(g, s), "FFN-1 gemm");
+    RUN_GEMM(SDV2_TAG_FFN1, "FFN-1 gemm");
     g.a = ws.u;
     g.w = static_cast<const bf16*>(w->W_2);
     g.bias = w->b_2;
@@ -1045,10 +1058,14 @@ int32_t run_block(const sdv2_model_cfg* cfg, const sdv2_block_weights* w, sdv2_k
         ln1.shift_b = e0 + 0 * C;
         ln1.scale_a = next_w->mod_table + 1 * C;
         ln1.scale_b = e0 + 1 * C;
-        RUN(SDV2_TAG_FFN2, launch_gemm_then_layernorm(g, ln1, next_h_ready, s), "FFN-2 gemm");
+        RUN(SDV2_TAG_FFN2, launch_gemm_then_layernorm(g, ln1, next_h_ready, s, 1), "FFN-2 gemm");
+        if (gemm_splits_k(g))
+            RUN(SDV2_TAG_GEMM_REDUCE, launch_gemm_then_layernorm(g, ln1, next_h_ready, s, 2), "FFN-2 gemm (sum of the k parts)");
     } else {
-        RUN(SDV2_TAG_FFN2, launch_gemm(g, s), "FFN-2 gemm");
+        RUN_GEMM(SDV2_TAG_FFN2, "FFN-2 gemm");
     }
+#undef RUN_GEMM
+#undef RUN_ATTN
 #undef RUN
     return SDV2_OK;
 }
@@ -1515,6 +1532,31 @@ int32_t sdv2_prof_peak_copy(const void* src_dev, void* dst_dev, size_t bytes, vo
         return fail(SDV2_INVALID_ARG, "buffers must be 16-byte aligned");
     HIP_TRY(launch_peak_copy(src_dev, dst_dev, bytes, static_cast<hipStream_t>(hip_stream)), "peak copy kernel");
     return SDV2_OK;
+}
+
+int32_t sdv2_prof_kernel_name(int32_t kind, int32_t B, int32_t L, int32_t a0, int32_t a1, int32_t a2, char* out,
+                              size_t capacity) {
+    if (!out || capacity < 8) return fail(SDV2_INVALID_ARG, "out is null or too small");
+    if (kind == 0) {                                   // GEMM: rows = B * L, a0 = N, a1 = K, a2 = epilogue
+        if (B <= 0 || L <= 0 || a0 <= 0 || a1 <= 0 || a2 < 0 || a2 > 3) return fail(SDV2_INVALID_ARG, "bad GEMM shape");
+        gemm_plan_name(B * L, a0, a1, a2, out, capacity);
+        return SDV2_OK;
+    }
+    if (kind == 1) {                                   // attention: a0 = heads, a1 = keys, a2 = capacity in slots
+        if (B <= 0 || B > SDV2_MAX_BATCH || L <= 0 || a0 <= 0 || a1 <= 0 || a2 < a1) return fail(SDV2_INVALID_ARG, "bad attention shape");
+        AttnArgs a;
+        memset(&a, 0, sizeof(a));
+        a.B = B;
+        a.L = L;
+        a.H = a0;
+        for (int b = 0; b < B; ++b) {
+            a.kv_len[b] = a1;
+            a.cap[b] = a2;
+        }
+        attention_plan_name(a, out, capacity);
+        return SDV2_OK;
+    }
+    return fail(SDV2_INVALID_ARG, "kind must be 0 (GEMM) or 1 (attention)");
 }
 
 int32_t sdv2_prof_begin(int32_t max_samples) {

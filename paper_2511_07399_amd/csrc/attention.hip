@@ -30,6 +30,7 @@
 //     write normalised partial outputs with their (max, sum); a small kernel merges them.
 #include "common.h"
 
+#include <stdio.h>
 #include <stdlib.h>
 
 #include <mutex>
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
     const int split = bz - b * a.splits;
     const int C = a.H * D;
 
-    const int kv_len = a.desc ? a.desc->kv_len[b] : a.kv_len[b];
+    const int kv_len = __builtin_amdgcn_readfirstlane(a.desc ? a.desc->kv_len[b] : a.kv_len[b]);
     const int cap = a.cap[b];
     const int n_tiles = (kv_len + KT - 1) / KT;
     const int t0 = (int)((long long)split * n_tiles / a.splits);
@@ -718,7 +719,16 @@ size_t attention_workspace_bytes(int B, int L, int C, int max_kv_len) {
     return (size_t)splits * rows * C * sizeof(float) + (size_t)splits * rows * H * 2 * sizeof(float);
 }
 
-hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
+void attention_plan_name(const AttnArgs& a, char* out, size_t cap) {
+    int max_kv = 0;
+    for (int b = 0; b < a.B; ++b) max_kv = a.kv_len[b] > max_kv ? a.kv_len[b] : max_kv;
+    if (attention_plan_key_split(a)) snprintf(out, cap, "attention_ks_kernel<2, 4>");
+    else snprintf(out, cap, "attention_kernel<%d>", attention_plan_waves(a.B, a.L, a.H, max_kv));
+}
+
+bool attention_has_merge_pass(const AttnArgs& a) { return a.splits > 1 && !attention_plan_key_split(a); }
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s, int part) {
     const size_t smem = (size_t)2 * K_TILE_BYTES + 2 * V_TILE_BYTES;
     constexpr size_t smem_ks = (size_t)4 * 32768 + 2 * 8 * 32 * sizeof(float);     // four 32 KB stages + the (m, l) exchange
     static std::once_flag attr_once;
@@ -736,19 +746,23 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
     if (attr_err != hipSuccess || attributes_only()) return attr_err;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
     if (attention_plan_key_split(a)) {
+        if (part == 2) return hipSuccess;
         dim3 grid((a.L + 63) / 64, a.H, a.B);
         hipLaunchKernelGGL((attention_ks_kernel<2, 4>), grid, dim3(512), smem_ks, s, a, scale_log2e);
         return hipGetLastError();
     }
-    int max_kv = 0;
-    for (int b = 0; b < a.B; ++b) max_kv = a.kv_len[b] > max_kv ? a.kv_len[b] : max_kv;
-    const int nw = attention_plan_waves(a.B, a.L, a.H, max_kv);
-    const int QT = 32 * nw;
-    dim3 grid((a.L + QT - 1) / QT, a.H, a.B * a.splits);
-    if (nw == 8) hipLaunchKernelGGL(attention_kernel<8>, grid, dim3(512), smem, s, a, scale_log2e);
-    else hipLaunchKernelGGL(attention_kernel<4>, grid, dim3(256), smem, s, a, scale_log2e);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (part != 2) {
+        int max_kv = 0;
+        for (int b = 0; b < a.B; ++b) max_kv = a.kv_len[b] > max_kv ? a.kv_len[b] : max_kv;
+        const int nw = attention_plan_waves(a.B, a.L, a.H, max_kv);
+        const int QT = 32 * nw;
+        dim3 grid((a.L + QT - 1) / QT, a.H, a.B * a.splits);
+        if (nw == 8) hipLaunchKernelGGL(attention_kernel<8>, grid, dim3(512), smem, s, a, scale_log2e);
+        else hipLaunchKernelGGL(attention_kernel<4>, grid, dim3(256), smem, s, a, scale_log2e);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess || part == 1) return e;
     if (a.splits > 1) {
         const size_t n = (size_t)a.B * a.L * (a.H * D / 4);
         hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a);

@@ -64,6 +64,8 @@ struct GemmArgs {
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 // fp32 partial sums the planned launch of an [M, K] x [N, K] product needs (0: its plan does not split k)
 size_t gemm_splitk_floats(int M, int N, int K, int epilogue);
+// Name of the kernel instantiation the plan picks for a shape, spelled as a profiler prints it (benchmark only).
+void gemm_plan_name(int M, int N, int K, int epilogue, char* out, size_t cap);
 // Tuning hooks (tests and sweeps): a tile plan that replaces the planner's for every shape; false if not understood.
 bool set_gemm_tile_override(const char* spec);
 
@@ -93,7 +95,9 @@ int attention_plan_splits(int B, int L, int H, int max_kv_len);
 // Tuning hooks: waves per workgroup (4, 8; 0 = planner) and key-range splits (0 = planner); -1 leaves a value as is.
 void set_attention_overrides(int waves, int splits);
 size_t attention_workspace_bytes(int B, int L, int C, int max_kv_len);
-hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s, int part = 0);   // part 1: the kernel; 2: the merge pass only
+bool attention_has_merge_pass(const AttnArgs& a);
+void attention_plan_name(const AttnArgs& a, char* out, size_t cap);      // only B, L, H, kv_len and cap are read
 
 // LayerNorm over C with an affine that is either adaLN modulation or a plain (gamma, beta).
 struct LnArgs {
@@ -115,7 +119,10 @@ hipError_t launch_layernorm(const LnArgs& a, hipStream_t s);
 // plan splits k, the pass that adds the parts owns whole rows and also writes that LayerNorm's output (ln.x is
 // ignored: the rows are g.out's; ln.rows = g.M, ln.C = g.N).  *ln_done tells whether it did; if not, the caller
 // launches the LayerNorm itself.
-hipError_t launch_gemm_then_layernorm(const GemmArgs& g, const LnArgs& ln, bool* ln_done, hipStream_t s);
+// part 0: everything; 1: only the kernel on the matrix cores; 2: only the pass that adds the k parts.
+hipError_t launch_gemm_then_layernorm(const GemmArgs& g, const LnArgs& ln, bool* ln_done, hipStream_t s, int part = 0);
+hipError_t launch_gemm_part(const GemmArgs& g, hipStream_t s, int part);
+bool gemm_splits_k(const GemmArgs& g);               // whether the planned launch has such a second pass
 
 // In-place RMSNorm over C of bf16 rows, times gain.
 hipError_t launch_rmsnorm_inplace(bf16* x, const float* gain, int rows, int C, int ld, float eps, hipStream_t s);

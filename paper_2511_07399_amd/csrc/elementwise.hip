@@ -26,7 +26,10 @@ __device__ __forceinline__ int slot_of(long long g, int S, int W) {
 // and (x - x[0])^2 (shifting by the row's first element keeps the fp32 variance exact enough whatever the
 // row's mean); the two waves of a row exchange their partial sums through LDS.
 // LN_MAXV = float4 values a lane keeps in registers: C <= 512 * LN_MAXV.
-template <int LN_MAXV>
+// EARLY: scale and shift are fetched together with the row instead of after the reduction.  With few rows the kernel
+// is a chain of latencies and theirs would come on top of the row's; with many rows it is bound by bandwidth and the
+// extra registers would only cost occupancy.
+template <int LN_MAXV, bool EARLY>
 __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
     __shared__ float part[2][2][2];                       // [row in workgroup][wave of the row][sum, sum of squares]
     const int lane = threadIdx.x & 63;
@@ -41,12 +44,30 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
     const f32x4* xp = reinterpret_cast<const f32x4*>(a.x + (size_t)row * a.C);
     const float pivot = a.x[(size_t)row * a.C];
     f32x4 v[LN_MAXV];
+    f32x4 sc[EARLY ? LN_MAXV : 1], sh[EARLY ? LN_MAXV : 1];
+    const int stream = row / a.rows_per_stream;
+    auto fetch_affine = [&](int c, f32x4& scv, f32x4& shv) {
+        scv = *reinterpret_cast<const f32x4*>(a.scale_a + c);
+        shv = *reinterpret_cast<const f32x4*>(a.shift_a + c);
+        if (a.scale_b != nullptr) {
+            scv += *reinterpret_cast<const f32x4*>(a.scale_b + (size_t)stream * a.b_stride + c);
+            shv += *reinterpret_cast<const f32x4*>(a.shift_b + (size_t)stream * a.b_stride + c);
+            scv += 1.0f;
+        }
+    };
     float sum = 0.0f, sq = 0.0f;
 #pragma unroll
     for (int i = 0; i < LN_MAXV; ++i) {
         const int idx = t + 128 * i;
         if (idx < nvec) {
             v[i] = xp[idx];
+            if (EARLY) fetch_affine(idx * 4, sc[i], sh[i]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < LN_MAXV; ++i) {
+        const int idx = t + 128 * i;
+        if (idx < nvec) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float d = v[i][e] - pivot;
@@ -70,29 +91,24 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
     const float rstd = rsqrtf(var + a.eps);
     const float mean = pivot + dmean;
     if (!live) return;
-    const int stream = row / a.rows_per_stream;
     bf16* op = a.out + (size_t)row * a.C;
 #pragma unroll
     for (int i = 0; i < LN_MAXV; ++i) {
         const int idx = t + 128 * i;
         if (idx < nvec) {
-            const int c = idx * 4;
-            f32x4 sc = *reinterpret_cast<const f32x4*>(a.scale_a + c);
-            f32x4 sh = *reinterpret_cast<const f32x4*>(a.shift_a + c);
-            if (a.scale_b != nullptr) {
-                sc += *reinterpret_cast<const f32x4*>(a.scale_b + (size_t)stream * a.b_stride + c);
-                sh += *reinterpret_cast<const f32x4*>(a.shift_b + (size_t)stream * a.b_stride + c);
-                sc += 1.0f;
-            }
+            if (!EARLY) fetch_affine(idx * 4, sc[0], sh[0]);
+            const f32x4 scv = sc[EARLY ? i : 0], shv = sh[EARLY ? i : 0];
             bf16x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (bf16)((v[i][e] - mean) * rstd * sc[e] + sh[e]);
-            *reinterpret_cast<bf16x4*>(op + c) = o;
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)((v[i][e] - mean) * rstd * scv[e] + shv[e]);
+            *reinterpret_cast<bf16x4*>(op + idx * 4) = o;
         }
     }
 }
 
 // ------------------------------------------------------------------ RMSNorm in place on bf16 rows
+// One wavefront per row; the row (NV 16-byte pieces per lane) and the gains are fetched once and stay in registers.
+template <int NV>
 __global__ __launch_bounds__(256) void rmsnorm_inplace_kernel(bf16* x, const float* gain, int rows, int C, int ld,
                                                               float eps) {
     const int lane = threadIdx.x & 63;
@@ -100,18 +116,38 @@ __global__ __launch_bounds__(256) void rmsnorm_inplace_kernel(bf16* x, const flo
     if (row >= rows) return;
     bf16* xp = x + (size_t)row * ld;
     const int nvec = C >> 3;
+    bf16x8 v[NV];
+    f32x4 g0[NV], g1[NV];
     float sq = 0.0f;
-    for (int idx = lane; idx < nvec; idx += 64) {
-        const bf16x8 v = *reinterpret_cast<const bf16x8*>(xp + idx * 8);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sq += (float)v[e] * (float)v[e];
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + 64 * i;
+        if (idx < nvec) {
+            v[i] = *reinterpret_cast<const bf16x8*>(xp + idx * 8);
+            g0[i] = *reinterpret_cast<const f32x4*>(gain + idx * 8);
+            g1[i] = *reinterpret_cast<const f32x4*>(gain + idx * 8 + 4);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if (lane + 64 * i < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sq += (float)v[i][e] * (float)v[i][e];
+        }
     }
     const float r = rsqrtf(wave_sum(sq) / (float)C + eps);
-    for (int idx = lane; idx < nvec; idx += 64) {
-        bf16x8 v = *reinterpret_cast<const bf16x8*>(xp + idx * 8);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = (bf16)((float)v[e] * r * gain[idx * 8 + e]);
-        *reinterpret_cast<bf16x8*>(xp + idx * 8) = v;
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + 64 * i;
+        if (idx < nvec) {
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o[e] = (bf16)((float)v[i][e] * r * g0[i][e]);
+                o[e + 4] = (bf16)((float)v[i][e + 4] * r * g1[i][e]);
+            }
+            *reinterpret_cast<bf16x8*>(xp + idx * 8) = o;
+        }
     }
 }
 
@@ -325,21 +361,33 @@ __global__ __launch_bounds__(256) void gemv_kernel(const float* x, const bf16* w
 
 }  // namespace
 
-hipError_t launch_layernorm(const LnArgs& a, hipStream_t s) {
+template <bool EARLY>
+static hipError_t launch_layernorm_t(const LnArgs& a, hipStream_t s) {
     const dim3 grid((a.rows + 1) / 2), block(256);
     const int nv = (a.C + 511) / 512;                   // float4 values per lane: 128 lanes per row
-    if (nv <= 1) hipLaunchKernelGGL(layernorm_kernel<1>, grid, block, 0, s, a);
-    else if (nv <= 3) hipLaunchKernelGGL(layernorm_kernel<3>, grid, block, 0, s, a);
-    else if (nv <= 4) hipLaunchKernelGGL(layernorm_kernel<4>, grid, block, 0, s, a);
-    else if (nv <= 6) hipLaunchKernelGGL(layernorm_kernel<6>, grid, block, 0, s, a);
-    else if (nv <= 10) hipLaunchKernelGGL(layernorm_kernel<10>, grid, block, 0, s, a);
-    else if (nv <= 16) hipLaunchKernelGGL(layernorm_kernel<16>, grid, block, 0, s, a);
+    if (nv <= 1) hipLaunchKernelGGL((layernorm_kernel<1, EARLY>), grid, block, 0, s, a);
+    else if (nv <= 3) hipLaunchKernelGGL((layernorm_kernel<3, EARLY>), grid, block, 0, s, a);
+    else if (nv <= 4) hipLaunchKernelGGL((layernorm_kernel<4, EARLY>), grid, block, 0, s, a);
+    else if (nv <= 6) hipLaunchKernelGGL((layernorm_kernel<6, EARLY>), grid, block, 0, s, a);
+    else if (nv <= 10) hipLaunchKernelGGL((layernorm_kernel<10, EARLY>), grid, block, 0, s, a);
+    else if (nv <= 16) hipLaunchKernelGGL((layernorm_kernel<16, EARLY>), grid, block, 0, s, a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
+hipError_t launch_layernorm(const LnArgs& a, hipStream_t s) {
+    return a.rows <= 4096 ? launch_layernorm_t<true>(a, s) : launch_layernorm_t<false>(a, s);
+}
+
 hipError_t launch_rmsnorm_inplace(bf16* x, const float* gain, int rows, int C, int ld, float eps, hipStream_t s) {
-    hipLaunchKernelGGL(rmsnorm_inplace_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, x, gain, rows, C, ld, eps);
+    const dim3 grid((rows + 3) / 4), block(256);
+    const int nv = (C + 511) / 512;                     // 16-byte pieces per lane
+    if (nv <= 1) hipLaunchKernelGGL(rmsnorm_inplace_kernel<1>, grid, block, 0, s, x, gain, rows, C, ld, eps);
+    else if (nv <= 3) hipLaunchKernelGGL(rmsnorm_inplace_kernel<3>, grid, block, 0, s, x, gain, rows, C, ld, eps);
+    else if (nv <= 6) hipLaunchKernelGGL(rmsnorm_inplace_kernel<6>, grid, block, 0, s, x, gain, rows, C, ld, eps);
+    else if (nv <= 10) hipLaunchKernelGGL(rmsnorm_inplace_kernel<10>, grid, block, 0, s, x, gain, rows, C, ld, eps);
+    else if (nv <= 16) hipLaunchKernelGGL(rmsnorm_inplace_kernel<16>, grid, block, 0, s, x, gain, rows, C, ld, eps);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -912,32 +912,29 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
 }  // namespace
 
 namespace {
-// The same sum of the k parts for a residual epilogue whose result is LayerNorm-ed next: two waves own a row (two
-// rows per workgroup, as in the LayerNorm kernel), add the parts in k order, apply bias, gate and residual, store the
-// new fp32 row, and normalise it from the registers: one launch and one read of x less than reduce + LayerNorm.
+// The same sum of the k parts for a residual epilogue whose result is LayerNorm-ed next: a workgroup of four waves
+// owns a row, adds the parts in k order, applies bias, gate and residual, stores the new fp32 row, and normalises it
+// from the registers: one launch and one read of x less than reduce + LayerNorm.  (One row per workgroup: the pass
+// reads splitk + 1 fp32 rows per output row, and with fewer, fatter workgroups it ran at 2.5 TB/s.)
 template <int NV>
 __global__ __launch_bounds__(256) void splitk_reduce_ln_kernel(GemmArgs g, int splitk, LnArgs ln) {
-    __shared__ float part[2][2][2];
+    __shared__ float part[4][2];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int rw = wave >> 1;
-    const int half = wave & 1;
-    const int t = half * 64 + lane;
-    const int row_raw = blockIdx.x * 2 + rw;
-    const bool live = row_raw < g.M;
-    const int row = live ? row_raw : g.M - 1;             // a spare half workgroup recomputes the last row, stores nothing
+    const int t = threadIdx.x;
+    const int row = blockIdx.x;
     const int nvec = g.N >> 2;
     const size_t plane = (size_t)g.M * g.N;
     float* xrow = reinterpret_cast<float*>(g.out) + (size_t)row * g.N;
     const float* prow = g.splitk_partials + (size_t)row * g.N;
     const int stream = row / g.rows_per_gate;
+    const int ln_stream = row / ln.rows_per_stream;
     const float pivot = xrow[0];                          // any value near the row's mean: read before the row is rewritten
-    f32x4 v[NV];
-    float sum = 0.0f, sq = 0.0f;
-    __syncthreads();                                      // every thread of the row has read the pivot before x changes
+    f32x4 v[NV], sc[NV], sh[NV];
+    // everything the row needs is requested at once: the parts, x, bias and gate, and the LayerNorm's scale and shift
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = t + 128 * i;
+        const int idx = t + 256 * i;
         if (idx < nvec) {
             const int c = idx * 4;
             f32x4 acc = *reinterpret_cast<const f32x4*>(prow + c);
@@ -947,7 +944,22 @@ __global__ __launch_bounds__(256) void splitk_reduce_ln_kernel(GemmArgs g, int s
                 acc *= *reinterpret_cast<const f32x4*>(g.gate_a + c) +
                        *reinterpret_cast<const f32x4*>(g.gate_b + (size_t)stream * g.gate_b_stride + c);
             v[i] = *reinterpret_cast<const f32x4*>(xrow + c) + acc;
-            if (live) *reinterpret_cast<f32x4*>(xrow + c) = v[i];
+            sc[i] = *reinterpret_cast<const f32x4*>(ln.scale_a + c);
+            sh[i] = *reinterpret_cast<const f32x4*>(ln.shift_a + c);
+            if (ln.scale_b != nullptr) {
+                sc[i] += *reinterpret_cast<const f32x4*>(ln.scale_b + (size_t)ln_stream * ln.b_stride + c);
+                sh[i] += *reinterpret_cast<const f32x4*>(ln.shift_b + (size_t)ln_stream * ln.b_stride + c);
+                sc[i] += 1.0f;
+            }
+        }
+    }
+    __syncthreads();                                      // every thread of the row has read the pivot before x changes
+    float sum = 0.0f, sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = t + 256 * i;
+        if (idx < nvec) {
+            *reinterpret_cast<f32x4*>(xrow + idx * 4) = v[i];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float d = v[i][e] - pivot;
@@ -959,36 +971,26 @@ __global__ __launch_bounds__(256) void splitk_reduce_ln_kernel(GemmArgs g, int s
     sum = wave_sum(sum);
     sq = wave_sum(sq);
     if (lane == 0) {
-        part[rw][half][0] = sum;
-        part[rw][half][1] = sq;
+        part[wave][0] = sum;
+        part[wave][1] = sq;
     }
     __syncthreads();
-    sum = part[rw][0][0] + part[rw][1][0];
-    sq = part[rw][0][1] + part[rw][1][1];
+    sum = (part[0][0] + part[1][0]) + (part[2][0] + part[3][0]);
+    sq = (part[0][1] + part[1][1]) + (part[2][1] + part[3][1]);
     const float inv_c = 1.0f / (float)g.N;
     const float dmean = sum * inv_c;
     const float var = fmaxf(sq * inv_c - dmean * dmean, 0.0f);
     const float rstd = rsqrtf(var + ln.eps);
     const float mean = pivot + dmean;
-    if (!live) return;
-    const int ln_stream = row / ln.rows_per_stream;
     bf16* op = ln.out + (size_t)row * g.N;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = t + 128 * i;
+        const int idx = t + 256 * i;
         if (idx < nvec) {
-            const int c = idx * 4;
-            f32x4 sc = *reinterpret_cast<const f32x4*>(ln.scale_a + c);
-            f32x4 sh = *reinterpret_cast<const f32x4*>(ln.shift_a + c);
-            if (ln.scale_b != nullptr) {
-                sc += *reinterpret_cast<const f32x4*>(ln.scale_b + (size_t)ln_stream * ln.b_stride + c);
-                sh += *reinterpret_cast<const f32x4*>(ln.shift_b + (size_t)ln_stream * ln.b_stride + c);
-                sc += 1.0f;
-            }
             bf16x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (bf16)((v[i][e] - mean) * rstd * sc[e] + sh[e]);
-            *reinterpret_cast<bf16x4*>(op + c) = o;
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)((v[i][e] - mean) * rstd * sc[i][e] + sh[i][e]);
+            *reinterpret_cast<bf16x4*>(op + idx * 4) = o;
         }
     }
 }
@@ -1003,24 +1005,27 @@ static int usable_splitk(const GemmArgs& g, const TilePlan& p) {
     return splitk;
 }
 
-static hipError_t launch_gemm_impl(const GemmArgs& g, const LnArgs* ln, bool* ln_done, hipStream_t s) {
+// part 0: the whole product; 1: only the kernel on the matrix cores; 2: only the pass that adds the k parts (nothing
+// when the plan does not split).  The benchmark times the two parts separately.
+static hipError_t launch_gemm_impl(const GemmArgs& g, const LnArgs* ln, bool* ln_done, hipStream_t s, int part = 0) {
     TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue);
     tile_override(&p);
     const int splitk = usable_splitk(g, p);
-    hipError_t e;
-    if (p.dma) e = launch_dma_config(g, p.dma, splitk, s);
-    else if (p.pf == 3) e = p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
-    else e = p.tm == 1 ? launch_tn<1, 2>(g, p.tn, splitk, s) : launch_tn<2, 2>(g, p.tn, splitk, s);
-    if (e != hipSuccess || splitk == 1 || attributes_only()) return e;
-    const int nv = (g.N + 511) / 512;                   // float4 values per lane with 128 lanes per row
-    if (ln != nullptr && (g.epilogue == kEpiGatedResidual || g.epilogue == kEpiResidual) && nv <= 16) {
-        const dim3 grid((g.M + 1) / 2), block(256);
+    hipError_t e = hipSuccess;
+    if (part != 2) {
+        if (p.dma) e = launch_dma_config(g, p.dma, splitk, s);
+        else if (p.pf == 3) e = p.tm == 1 ? launch_tn<1, 3>(g, p.tn, splitk, s) : launch_tn<2, 3>(g, p.tn, splitk, s);
+        else e = p.tm == 1 ? launch_tn<1, 2>(g, p.tn, splitk, s) : launch_tn<2, 2>(g, p.tn, splitk, s);
+    }
+    if (e != hipSuccess || splitk == 1 || attributes_only() || part == 1) return e;
+    const int nv = (g.N + 1023) / 1024;                 // float4 values per thread with 256 threads per row
+    if (ln != nullptr && (g.epilogue == kEpiGatedResidual || g.epilogue == kEpiResidual) && nv <= 8) {
+        const dim3 grid(g.M), block(256);
         if (nv <= 1) hipLaunchKernelGGL(splitk_reduce_ln_kernel<1>, grid, block, 0, s, g, splitk, *ln);
+        else if (nv <= 2) hipLaunchKernelGGL(splitk_reduce_ln_kernel<2>, grid, block, 0, s, g, splitk, *ln);
         else if (nv <= 3) hipLaunchKernelGGL(splitk_reduce_ln_kernel<3>, grid, block, 0, s, g, splitk, *ln);
-        else if (nv <= 4) hipLaunchKernelGGL(splitk_reduce_ln_kernel<4>, grid, block, 0, s, g, splitk, *ln);
-        else if (nv <= 6) hipLaunchKernelGGL(splitk_reduce_ln_kernel<6>, grid, block, 0, s, g, splitk, *ln);
-        else if (nv <= 10) hipLaunchKernelGGL(splitk_reduce_ln_kernel<10>, grid, block, 0, s, g, splitk, *ln);
-        else hipLaunchKernelGGL(splitk_reduce_ln_kernel<16>, grid, block, 0, s, g, splitk, *ln);
+        else if (nv <= 5) hipLaunchKernelGGL(splitk_reduce_ln_kernel<5>, grid, block, 0, s, g, splitk, *ln);
+        else hipLaunchKernelGGL(splitk_reduce_ln_kernel<8>, grid, block, 0, s, g, splitk, *ln);
         *ln_done = true;
         return hipGetLastError();
     }
@@ -1031,9 +1036,34 @@ static hipError_t launch_gemm_impl(const GemmArgs& g, const LnArgs* ln, bool* ln
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) { return launch_gemm_impl(g, nullptr, nullptr, s); }
 
-hipError_t launch_gemm_then_layernorm(const GemmArgs& g, const LnArgs& ln, bool* ln_done, hipStream_t s) {
+// Name of the kernel instantiation the plan picks for a shape, spelled as a profiler prints it.
+void gemm_plan_name(int M, int N, int K, int epilogue, char* out, size_t cap) {
+    TilePlan p = plan_tiles(M, N, K, epilogue);
+    tile_override(&p);
+    static const int kDma[kDmaConfigs + 1][5] = {{0, 0, 0, 0, 0}, {4, 2, 2, 4, 2}, {2, 4, 4, 2, 2}, {2, 4, 2, 2, 3}, {4, 2, 2, 2, 3},
+                                                 {4, 2, 2, 4, 0}, {2, 4, 4, 2, 0}, {4, 1, 1, 2, 3}, {4, 1, 1, 2, 4}, {4, 2, 1, 1, 4},
+                                                 {2, 2, 1, 2, 4}, {2, 2, 2, 2, 3}, {2, 4, 2, 1, 3}, {4, 1, 1, 5, 2}, {4, 1, 1, 5, 3},
+                                                 {4, 1, 1, 6, 3}, {4, 2, 1, 3, 3}};
+    if (p.dma == 5 || p.dma == 6)
+        snprintf(out, cap, "gemm_ring_kernel<%d, %d, %d, %d>", kDma[p.dma][0], kDma[p.dma][1], kDma[p.dma][2], kDma[p.dma][3]);
+    else if (p.dma)
+        snprintf(out, cap, "gemm_dma_kernel<%d, %d, %d, %d, %d>", kDma[p.dma][0], kDma[p.dma][1], kDma[p.dma][2], kDma[p.dma][3],
+                 kDma[p.dma][4]);
+    else
+        snprintf(out, cap, "gemm_kernel<%d, %d, 64, %d>", p.tm, p.tn, p.pf);
+}
+
+hipError_t launch_gemm_then_layernorm(const GemmArgs& g, const LnArgs& ln, bool* ln_done, hipStream_t s, int part) {
     *ln_done = false;
-    return launch_gemm_impl(g, &ln, ln_done, s);
+    return launch_gemm_impl(g, &ln, ln_done, s, part);
+}
+
+hipError_t launch_gemm_part(const GemmArgs& g, hipStream_t s, int part) { return launch_gemm_impl(g, nullptr, nullptr, s, part); }
+
+bool gemm_splits_k(const GemmArgs& g) {
+    TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue);
+    tile_override(&p);
+    return usable_splitk(g, p) > 1;
 }
 
 size_t gemm_splitk_floats(int M, int N, int K, int epilogue) {
