@@ -131,3 +131,41 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_stream_batch_handle_and_planner_hooks_on_the_host(lib):
+    """Host-only parts of the newer entry points: stream-batch handle validation (nothing is launched), the planner's
+    kernel names, and the tuning hook's parsing."""
+    cfg = binding.model_cfg(512, 4, 2048, 8, 16, 64, 1)
+    need = binding.stream_batch_rows_bytes(cfg, 4, 1)
+    assert need >= 4 * 128 * 512 * 4
+    assert binding.stream_batch_rows_bytes(cfg, 9, 1) == 0            # more depths than SDV2_MAX_BATCH
+    fake = C.c_void_p(0x100000)                                       # never dereferenced by create
+    h = C.c_void_p()
+    ids = (C.c_int32 * 4)(0, 1, 2, 3)
+    same = (C.c_int32 * 4)(0, 1, 1, 3)
+    f = lib.sdv2_stream_batch_create
+    assert f(C.byref(cfg), 4, same, 1, fake, need, C.byref(h)) == binding.INVALID_ARG
+    assert f(C.byref(cfg), 4, ids, 1, fake, need - 256, C.byref(h)) == binding.WORKSPACE_TOO_SMALL
+    assert f(C.byref(cfg), 4, ids, 1, C.c_void_p(0x100010), need, C.byref(h)) == binding.INVALID_ARG     # alignment
+    assert f(C.byref(cfg), 0, ids, 1, fake, need, C.byref(h)) == binding.INVALID_ARG
+    assert f(C.byref(cfg), 4, ids, 1, fake, need, C.byref(h)) == binding.OK
+    assert lib.sdv2_stream_batch_reset(h) == binding.OK
+    assert lib.sdv2_stream_batch_destroy(h) == binding.OK
+    assert lib.sdv2_denoise_graph_state_bytes() >= 8 * (8 + 4 + 4 + 4)
+    # the planner's kernel names: large shapes take the 256 x 256 ring kernel, the single-chunk attention of the 1.3B
+    # block the key-split form, a capacity that is no multiple of 128 the one-key-stream form
+    assert binding.prof_kernel_name("gemm", 4, 4680, 13824, 5120, 1).startswith("gemm_ring_kernel<")
+    assert binding.prof_kernel_name("attention", 1, 1024, 12, 3072, 3072) == "attention_ks_kernel<2, 4>"
+    assert binding.prof_kernel_name("attention", 1, 1024, 12, 3072, 3136).startswith("attention_kernel<")
+    assert binding.prof_kernel_name("attention", 4, 4680, 40, 10920, 10944) == "attention_kernel<8>"
+    binding.tuning_set("gemm_tile", "1,3")
+    try:
+        assert binding.prof_kernel_name("gemm", 4, 4680, 13824, 5120, 1) == "gemm_kernel<1, 3, 64, 2>"
+    finally:
+        binding.tuning_set("gemm_tile", None)
+    for name, value in (("gemm_tile", "9,9"), ("attn_waves", "3"), ("no_such_knob", "1")):
+        with pytest.raises(binding.Sdv2Error) as e:
+            binding.tuning_set(name, value)
+        assert e.value.code == binding.INVALID_ARG
+    assert binding.gemm_noalloc_max_scratch_bytes() == 32 << 20
