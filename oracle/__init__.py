@@ -15,6 +15,8 @@ What it follows (StreamDiffusionV2):
   * the motion-aware noise scheduler (Section 4.1), in ``motion.py``;
   * the SLO-aware batching scheduler (Section 4.1), in ``slo.py``;
   * the stream batch over denoising steps (Section 4.2), in ``stream_batch.py``;
+  * latents in, latents out around the blocks (patch embedding, output head, few-step sampler update: none of them
+    is in the paper, all are this build's readings), in ``latent_io.py``;
   * a causal DiT of the Wan 2.1 / CausVid lineage (Section 5.1 "Models") whose
     per-layer cost is 24 b L_q C^2 + 4 b L_q L_kv C (Appendix B).
 
@@ -39,6 +41,15 @@ from .refresh import (  # noqa: F401
 )
 from .slo import latency_model, frequency, pick_batch  # noqa: F401
 from .stream_batch import StreamBatch  # noqa: F401
+from .latent_io import (  # noqa: F401
+    patchify,
+    unpatchify,
+    patch_embed,
+    output_head,
+    noise_latents,
+    sampler_update,
+    denoise_latents_step,
+)
 from .motion import (  # noqa: F401
     motion_intensity,
     normalized_motion,
@@ -56,6 +67,7 @@ from .dit_block import (  # noqa: F401
     text_kv_prepare,
     dit_block_forward,
     timestep_embedding,
+    timestep_vector,
     conditioning,
     denoise_step,
 )

@@ -193,6 +193,13 @@ def timestep_embedding(t, dim=256, dtype=np.float64):
     return np.concatenate([np.cos(arg), np.sin(arg)]).astype(dtype)
 
 
+def timestep_vector(mw, t, dtype=np.float64):
+    """tvec = Lin2(SiLU(Lin1(timestep_embedding(t)))), the ``[C]`` vector every modulation is made from."""
+    f = lambda a: np.asarray(a, dtype=dtype)
+    emb = timestep_embedding(t, f(mw["W_t1"]).shape[1], dtype)
+    return linear(silu(linear(emb, f(mw["W_t1"]), f(mw["b_t1"]))), f(mw["W_t2"]), f(mw["b_t2"]))
+
+
 def conditioning(mw, t=None, tvec=None, dtype=np.float64):
     """Timestep -> tvec -> e0 ``[6, C]``.
 
@@ -201,8 +208,7 @@ def conditioning(mw, t=None, tvec=None, dtype=np.float64):
     """
     f = lambda a: np.asarray(a, dtype=dtype)
     if tvec is None:
-        emb = timestep_embedding(t, f(mw["W_t1"]).shape[1], dtype)
-        tvec = linear(silu(linear(emb, f(mw["W_t1"]), f(mw["b_t1"]))), f(mw["W_t2"]), f(mw["b_t2"]))
+        tvec = timestep_vector(mw, t, dtype)
     tvec = f(tvec)
     C = tvec.shape[-1]
     return linear(silu(tvec), f(mw["W_mod"]), f(mw["b_mod"])).reshape(6, C)

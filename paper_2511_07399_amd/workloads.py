@@ -134,6 +134,26 @@ def model_weights(wl, base_seed=0, device="cpu"):
             for tid, (name, shape, kind) in enumerate(spec)}
 
 
+IO_LAYER = 10_001           # pseudo layer index for the patch-embedding and head weights
+LATENT_CHANNELS = 16        # VAE latent channels; a token covers 2 x 2 latent positions (64 numbers)
+
+
+def io_weights(wl, base_seed=0, device="cpu"):
+    """Patch-embedding and output-head weights: matrices bf16 ``[out, in]``, vectors fp32 (bf16-exact)."""
+    C, P = wl.C, 4 * LATENT_CHANNELS
+    spec = (("W_pe", (C, P), "matrix"), ("b_pe", (C,), "bias"), ("head_table", (2, C), "bias"),
+            ("W_head", (P, C), "matrix"), ("b_head", (P,), "bias"))
+    return {name: _draw(shape, kind, _seed(base_seed, IO_LAYER, tid), device)
+            for tid, (name, shape, kind) in enumerate(spec)}
+
+
+def latent_chunk(wl, chunk, stream=0, base_seed=0, device="cpu", kind=0):
+    """A latent chunk ``[16, frames, 2 grid_h, 2 grid_w]`` ~ N(0,1), fp32 holding bf16-exact values (kind 0: the clean
+    input, 1, 2, ...: the noise drawn for denoising step kind - 1)."""
+    return _normal((LATENT_CHANNELS, wl.frames_per_chunk, 2 * wl.grid_h, 2 * wl.grid_w),
+                   base_seed * 1_000_003 + 600_000 + 7919 * chunk + 97 * kind + stream, device)
+
+
 def _normal(shape, seed, device="cpu"):
     g = torch.Generator(device=device)
     g.manual_seed(seed)
