@@ -422,6 +422,63 @@ int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg,
                                void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Latents in, latents out.  The paper runs its causal DiT on VAE latents in 1-4 denoising steps per chunk
+ * (Section 5.1), at 2 x 2 latent positions per token (Appendix B: 60 x 104 latent positions -> 1 560 tokens) and gives
+ * each incoming chunk a noise rate s_t (Section 4.1, motion-aware noise scheduler); it prints no formula for the
+ * steps between latents and the blocks' hidden state, so the ones below are this library's readings:
+ *   latents  z: dev fp32 [B][16][F][2 grid_h][2 grid_w]   (16 = SDV2_LATENT_CHANNELS; F = n_frames of the chunk)
+ *   patch embedding   token (f, r, c) gathers the 64 numbers z[ch][f][2r + dr][2c + dc], in the order (ch, dr, dc), and
+ *                     x = patch W_pe^T + b_pe        (a 3-D convolution with kernel and stride (1, 2, 2)); x fp32 [B, L, C]
+ *   output head       v = unpatch( (LN(x)(1 + scale) + shift) W_head^T + b_head ),  (shift, scale) = head_table + tvec[b],
+ *                     the 64 numbers of a token going back to where the patch embedding took them from
+ *   noise rate        (1 - s) x + s eps for a clean latent x and noise eps
+ *   sampler update    the blocks' output read as the velocity eps - x of the interpolation above:  x0 = z - sigma v;
+ *                     z_next = x0 when sigma_next = 0, else (1 - sigma_next) x0 + sigma_next eps_next (fresh noise,
+ *                     passed in); the timestep fed to the blocks at noise level sigma is 1000 sigma.
+ * sdv2_timestep_vector: tvec (dev fp32 [B, C]) of the timesteps, the first line of sdv2_conditioning; workspace
+ *   sdv2_conditioning_workspace_bytes.   sdv2_patch_embed / sdv2_output_head: workspace sdv2_latent_io_workspace_bytes.
+ * sdv2_noise_latents / sdv2_sampler_update: elementwise over B x elems_per_stream fp32 values with one rate (sigma,
+ *   sigma_next) per stream, host arrays [B]; z_next_dev may be z_dev; x0_dev is optional; eps_next_dev may be NULL when
+ *   every sigma_next is 0.
+ * sdv2_denoise_latents_step: timestep vector, patch embedding, sdv2_denoise_step (with that vector), output head and
+ *   sampler update in one call; z_dev is updated in place, chunks / kt_dev / vtt_dev as in sdv2_denoise_step, workspace
+ *   sdv2_denoise_latents_workspace_bytes(cfg, B, L).
+ * Errors: null pointers, B outside 1 .. SDV2_MAX_BATCH, rates outside [0, 1], sigma_next > sigma: SDV2_INVALID_ARG;
+ *   otherwise those of the calls they are made of.
+ * ------------------------------------------------------------------------------------------------ */
+#define SDV2_LATENT_CHANNELS 16
+typedef struct sdv2_io_weights {
+    uint32_t struct_size;
+    uint32_t reserved;
+    const void* W_pe;          /* bf16 [C, 64] */
+    const float* b_pe;         /* [C] */
+    const float* head_table;   /* [2, C]: shift, scale (added to tvec) */
+    const void* W_head;        /* bf16 [64, C] */
+    const float* b_head;       /* [64] */
+} sdv2_io_weights;
+int32_t sdv2_timestep_vector(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, int32_t B,
+                             const float* timesteps_host, float* tvec_dev, void* workspace_dev, size_t workspace_bytes,
+                             void* hip_stream);
+size_t sdv2_latent_io_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L);
+int32_t sdv2_patch_embed(const sdv2_model_cfg* cfg, const sdv2_io_weights* io, const float* z_dev, int32_t B,
+                         int32_t n_frames, float* x_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+int32_t sdv2_output_head(const sdv2_model_cfg* cfg, const sdv2_io_weights* io, const float* x_dev, const float* tvec_dev,
+                         int32_t B, int32_t n_frames, float* v_dev, void* workspace_dev, size_t workspace_bytes,
+                         void* hip_stream);
+int32_t sdv2_noise_latents(const float* x_dev, const float* eps_dev, float* out_dev, int32_t B, int64_t elems_per_stream,
+                           const float* rate_host, void* hip_stream);
+int32_t sdv2_sampler_update(const float* z_dev, const float* v_dev, const float* eps_next_dev, float* z_next_dev,
+                            float* x0_dev, int32_t B, int64_t elems_per_stream, const float* sigma_host,
+                            const float* sigma_next_host, void* hip_stream);
+size_t sdv2_denoise_latents_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L);
+int32_t sdv2_denoise_latents_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, const sdv2_io_weights* io,
+                                  sdv2_kv_cache* cache, float* z_dev, const float* eps_next_dev, float* x0_dev,
+                                  const float* sigma_host, const float* sigma_next_host,
+                                  const void* const* kt_dev, const void* const* vtt_dev,
+                                  const sdv2_chunk_desc* chunks, int32_t B,
+                                  void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------------
  * The two dense kernels on their own (used by the per-kernel parity tests and the benchmark).
  *
  * sdv2_gemm_bf16: out = epilogue(a W^T + bias).  a: bf16 [M, K]; w: bf16 [N, K]; bias fp32 [N] or NULL.

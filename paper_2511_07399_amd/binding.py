@@ -60,6 +60,11 @@ class CacheState(C.Structure):
                 ("oldest_slot", C.c_int32), ("next_slot", C.c_int32)]
 
 
+class IoWeights(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("reserved", C.c_uint32), ("W_pe", C.c_void_p), ("b_pe", C.c_void_p),
+                ("head_table", C.c_void_p), ("W_head", C.c_void_p), ("b_head", C.c_void_p)]
+
+
 class MotionCfg(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("k", C.c_int32), ("sigma", C.c_float), ("lam", C.c_float),
                 ("s_min", C.c_float), ("s_max", C.c_float), ("s_init", C.c_float)]
@@ -77,7 +82,9 @@ EXPORTS = (
     "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_prof_kernel_name", "sdv2_tuning_set", "sdv2_gemm_noalloc_max_scratch_bytes",
     "sdv2_gemm_bf16_noalloc", "sdv2_stream_batch_rows_bytes", "sdv2_stream_batch_create", "sdv2_stream_batch_destroy",
     "sdv2_stream_batch_reset", "sdv2_stream_batch_step", "sdv2_denoise_graph_state_bytes", "sdv2_denoise_graph_create",
-    "sdv2_denoise_graph_launch", "sdv2_denoise_graph_destroy",
+    "sdv2_denoise_graph_launch", "sdv2_denoise_graph_destroy", "sdv2_timestep_vector", "sdv2_latent_io_workspace_bytes",
+    "sdv2_patch_embed", "sdv2_output_head", "sdv2_noise_latents", "sdv2_sampler_update",
+    "sdv2_denoise_latents_workspace_bytes", "sdv2_denoise_latents_step",
 )
 
 LAUNCH_TAGS = ("adaLN-1", "QKV gemm", "rope+append", "self-attn", "out-proj gemm", "LN-3", "cross-q gemm",
@@ -166,6 +173,19 @@ def load_library():
                                            C.POINTER(C.c_float), C.POINTER(vp), C.POINTER(vp), f32p, C.POINTER(i32),
                                            C.POINTER(i32), vp, sz, vp]
     lib.sdv2_gemm_bf16_noalloc.argtypes = [vp, vp, f32p, vp, i32, i32, i32, i32, f32p, f32p, i32, i32, vp]
+    fp = C.POINTER(C.c_float)
+    lib.sdv2_timestep_vector.argtypes = [C.POINTER(ModelCfg), C.POINTER(ModelWeights), i32, fp, f32p, vp, sz, vp]
+    lib.sdv2_latent_io_workspace_bytes.restype = sz
+    lib.sdv2_latent_io_workspace_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
+    lib.sdv2_patch_embed.argtypes = [C.POINTER(ModelCfg), C.POINTER(IoWeights), f32p, i32, i32, f32p, vp, sz, vp]
+    lib.sdv2_output_head.argtypes = [C.POINTER(ModelCfg), C.POINTER(IoWeights), f32p, f32p, i32, i32, f32p, vp, sz, vp]
+    lib.sdv2_noise_latents.argtypes = [f32p, f32p, f32p, i32, C.c_int64, fp, vp]
+    lib.sdv2_sampler_update.argtypes = [f32p, f32p, f32p, f32p, f32p, i32, C.c_int64, fp, fp, vp]
+    lib.sdv2_denoise_latents_workspace_bytes.restype = sz
+    lib.sdv2_denoise_latents_workspace_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
+    lib.sdv2_denoise_latents_step.argtypes = [C.POINTER(ModelCfg), C.POINTER(ModelWeights), C.POINTER(IoWeights), vp,
+                                              f32p, f32p, f32p, fp, fp, C.POINTER(vp), C.POINTER(vp),
+                                              C.POINTER(ChunkDesc), i32, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -581,3 +601,76 @@ def denoise_graph_launch(h, timesteps, chunks):
 
 def denoise_graph_destroy(h):
     _check(_lib.sdv2_denoise_graph_destroy(h))
+
+
+# ------------------------------------------------------------------------------------------ latents in, latents out
+def io_weights(tensors):
+    """IoWeights struct from a dict of device tensors; the caller keeps the tensors alive."""
+    io = IoWeights()
+    io.struct_size = C.sizeof(IoWeights)
+    for name in ("W_pe", "b_pe", "head_table", "W_head", "b_head"):
+        t = tensors[name]
+        _dev(t, torch.bfloat16 if name.startswith("W_") else torch.float32)
+        setattr(io, name, t.data_ptr())
+    return io
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def timestep_vector(cfg, mw, timesteps, tvec, workspace):
+    _dev(tvec, torch.float32)
+    _check(_lib.sdv2_timestep_vector(C.byref(cfg), C.byref(mw), len(timesteps), _timesteps(timesteps), _ptr(tvec),
+                                     _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def latent_io_workspace_bytes(cfg, B, L):
+    load_library()
+    return int(_lib.sdv2_latent_io_workspace_bytes(C.byref(cfg), B, L))
+
+
+def patch_embed(cfg, io, z, x, workspace):
+    """z fp32 [B, 16, F, 2 grid_h, 2 grid_w] -> x fp32 [B, L, C]."""
+    _dev(z, torch.float32)
+    _dev(x, torch.float32)
+    _check(_lib.sdv2_patch_embed(C.byref(cfg), C.byref(io), _ptr(z), z.shape[0], z.shape[2], _ptr(x), _ptr(workspace),
+                                 _nbytes(workspace), _stream()))
+
+
+def output_head(cfg, io, x, tvec, v, workspace):
+    """x fp32 [B, L, C], tvec fp32 [B, C] -> v fp32 [B, 16, F, 2 grid_h, 2 grid_w]."""
+    _dev(x, torch.float32)
+    _dev(tvec, torch.float32)
+    _dev(v, torch.float32)
+    _check(_lib.sdv2_output_head(C.byref(cfg), C.byref(io), _ptr(x), _ptr(tvec), v.shape[0], v.shape[2], _ptr(v),
+                                 _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def noise_latents(x, eps, out, rates):
+    for t in (x, eps, out):
+        _dev(t, torch.float32)
+    B = len(rates)
+    _check(_lib.sdv2_noise_latents(_ptr(x), _ptr(eps), _ptr(out), B, x.numel() // B, _timesteps(rates), _stream()))
+
+
+def sampler_update(z, v, eps_next, z_next, x0, sigmas, sigmas_next):
+    for t in (z, v, z_next):
+        _dev(t, torch.float32)
+    B = len(sigmas)
+    _check(_lib.sdv2_sampler_update(_ptr(z), _ptr(v), _ptr(eps_next), _ptr(z_next), _ptr(x0), B, z.numel() // B,
+                                    _timesteps(sigmas), _timesteps(sigmas_next), _stream()))
+
+
+def denoise_latents_workspace_bytes(cfg, B, L):
+    load_library()
+    return int(_lib.sdv2_denoise_latents_workspace_bytes(C.byref(cfg), B, L))
+
+
+def denoise_latents_step(cfg, mw, io, cache, z, eps_next, x0, sigmas, sigmas_next, kt_array, vtt_array, chunks,
+                         workspace):
+    """z fp32 [B, 16, F, 2 grid_h, 2 grid_w], updated in place; x0 optional, same shape."""
+    _dev(z, torch.float32)
+    _check(_lib.sdv2_denoise_latents_step(C.byref(cfg), C.byref(mw), C.byref(io), cache, _ptr(z), _ptr(eps_next),
+                                          _ptr(x0), _timesteps(sigmas), _timesteps(sigmas_next), kt_array, vtt_array,
+                                          chunks, len(chunks), _ptr(workspace), _nbytes(workspace), _stream()))

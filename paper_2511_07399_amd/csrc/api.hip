@@ -1348,6 +1348,193 @@ int32_t sdv2_denoise_graph_launch(sdv2_denoise_graph* g, const float* timesteps_
 
 }  // extern "C"
 
+// ------------------------------------------------------------------------------------------ latents in, latents out
+namespace {
+bool io_weights_ok(const sdv2_io_weights* io) {
+    return io && io->struct_size == sizeof(sdv2_io_weights) && io->W_pe && io->b_pe && io->head_table && io->W_head && io->b_head;
+}
+constexpr int kPatchWidth = 4 * kLatentChannels;      // numbers per token: 16 channels x 2 x 2 latent positions
+}  // namespace
+
+extern "C" {
+
+int32_t sdv2_timestep_vector(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, int32_t B, const float* timesteps_host,
+                             float* tvec_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (B <= 0 || B > SDV2_MAX_BATCH) return fail(SDV2_INVALID_ARG, "B = %d out of range", B);
+    if (!mw || mw->struct_size != sizeof(sdv2_model_weights) || !mw->W_t1 || !mw->b_t1 || !mw->W_t2 || !mw->b_t2)
+        return fail(SDV2_INVALID_ARG, "timestep MLP weights missing");
+    if (!timesteps_host || !tvec_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (workspace_bytes < sdv2_conditioning_workspace_bytes(cfg, B)) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace too small");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    unsigned char* p = static_cast<unsigned char*>(workspace_dev);
+    float* emb = reinterpret_cast<float*>(p);
+    float* a1 = reinterpret_cast<float*>(p + align_up((size_t)B * cfg->t_dim * 4, 256));
+    HIP_TRY(launch_timestep_embedding(timesteps_host, nullptr, emb, B, cfg->t_dim, (double)cfg->rope_base, s), "timestep embedding");
+    HIP_TRY(launch_gemv(emb, static_cast<const bf16*>(mw->W_t1), mw->b_t1, a1, B, cfg->C, cfg->t_dim, 0, s), "timestep MLP 1");
+    HIP_TRY(launch_gemv(a1, static_cast<const bf16*>(mw->W_t2), mw->b_t2, tvec_dev, B, cfg->C, cfg->C, 1, s), "timestep MLP 2");
+    return SDV2_OK;
+}
+
+size_t sdv2_latent_io_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why) || B <= 0 || B > SDV2_MAX_BATCH || L <= 0) {
+        fail(SDV2_INVALID_ARG, "bad cfg, B or L");
+        return 0;
+    }
+    // the larger of: bf16 patches; bf16 normalised rows + fp32 head output
+    const size_t rows = (size_t)B * L;
+    return align_up(rows * cfg->C * 2, 256) + align_up(rows * kPatchWidth * 4, 256);
+}
+
+int32_t sdv2_patch_embed(const sdv2_model_cfg* cfg, const sdv2_io_weights* io, const float* z_dev, int32_t B, int32_t n_frames,
+                         float* x_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!io_weights_ok(io)) return fail(SDV2_INVALID_ARG, "bad io weights");
+    if (B <= 0 || B > SDV2_MAX_BATCH || n_frames <= 0) return fail(SDV2_INVALID_ARG, "bad B or n_frames");
+    if (!z_dev || !x_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    const int L = n_frames * cfg->grid_h * cfg->grid_w;
+    if (workspace_bytes < sdv2_latent_io_workspace_bytes(cfg, B, L)) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace too small");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    bf16* patches = static_cast<bf16*>(workspace_dev);
+    HIP_TRY(launch_patchify(z_dev, patches, B, n_frames, cfg->grid_h, cfg->grid_w, s), "patch gather");
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.a = patches;
+    g.w = static_cast<const bf16*>(io->W_pe);
+    g.bias = io->b_pe;
+    g.out = x_dev;
+    g.M = B * L;
+    g.N = cfg->C;
+    g.K = kPatchWidth;
+    g.epilogue = kEpiPartial;                        // plain fp32 store of acc + bias
+    g.rows_per_gate = 1;
+    HIP_TRY(launch_gemm(g, s), "patch-embedding gemm");
+    return SDV2_OK;
+}
+
+int32_t sdv2_output_head(const sdv2_model_cfg* cfg, const sdv2_io_weights* io, const float* x_dev, const float* tvec_dev,
+                         int32_t B, int32_t n_frames, float* v_dev, void* workspace_dev, size_t workspace_bytes,
+                         void* hip_stream) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!io_weights_ok(io)) return fail(SDV2_INVALID_ARG, "bad io weights");
+    if (B <= 0 || B > SDV2_MAX_BATCH || n_frames <= 0) return fail(SDV2_INVALID_ARG, "bad B or n_frames");
+    if (!x_dev || !tvec_dev || !v_dev || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    const int L = n_frames * cfg->grid_h * cfg->grid_w, C = cfg->C;
+    if (workspace_bytes < sdv2_latent_io_workspace_bytes(cfg, B, L)) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace too small");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    unsigned char* p = static_cast<unsigned char*>(workspace_dev);
+    bf16* h = reinterpret_cast<bf16*>(p);
+    float* tok = reinterpret_cast<float*>(p + align_up((size_t)B * L * C * 2, 256));
+    LnArgs ln;
+    ln.x = x_dev;
+    ln.out = h;
+    ln.rows = B * L;
+    ln.C = C;
+    ln.eps = cfg->eps;
+    ln.shift_a = io->head_table;
+    ln.scale_a = io->head_table + C;
+    ln.shift_b = tvec_dev;
+    ln.scale_b = tvec_dev;
+    ln.b_stride = C;
+    ln.rows_per_stream = L;
+    HIP_TRY(launch_layernorm(ln, s), "head LayerNorm");
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.a = h;
+    g.w = static_cast<const bf16*>(io->W_head);
+    g.bias = io->b_head;
+    g.out = tok;
+    g.M = B * L;
+    g.N = kPatchWidth;
+    g.K = C;
+    g.epilogue = kEpiPartial;
+    g.rows_per_gate = 1;
+    HIP_TRY(launch_gemm(g, s), "head gemm");
+    HIP_TRY(launch_unpatchify(tok, v_dev, B, n_frames, cfg->grid_h, cfg->grid_w, s), "un-patching");
+    return SDV2_OK;
+}
+
+int32_t sdv2_noise_latents(const float* x_dev, const float* eps_dev, float* out_dev, int32_t B, int64_t elems_per_stream,
+                           const float* rate_host, void* hip_stream) {
+    if (!x_dev || !eps_dev || !out_dev || !rate_host) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (B <= 0 || B > SDV2_MAX_BATCH || elems_per_stream <= 0) return fail(SDV2_INVALID_ARG, "bad B or size");
+    for (int b = 0; b < B; ++b)
+        if (!(rate_host[b] >= 0.0f && rate_host[b] <= 1.0f)) return fail(SDV2_INVALID_ARG, "noise rate of stream %d outside [0, 1]", b);
+    HIP_TRY(launch_noise(x_dev, eps_dev, out_dev, B, elems_per_stream, rate_host, static_cast<hipStream_t>(hip_stream)), "noise kernel");
+    return SDV2_OK;
+}
+
+int32_t sdv2_sampler_update(const float* z_dev, const float* v_dev, const float* eps_next_dev, float* z_next_dev, float* x0_dev,
+                            int32_t B, int64_t elems_per_stream, const float* sigma_host, const float* sigma_next_host,
+                            void* hip_stream) {
+    if (!z_dev || !v_dev || !z_next_dev || !sigma_host || !sigma_next_host) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (B <= 0 || B > SDV2_MAX_BATCH || elems_per_stream <= 0) return fail(SDV2_INVALID_ARG, "bad B or size");
+    for (int b = 0; b < B; ++b) {
+        if (!(sigma_host[b] >= 0.0f && sigma_host[b] <= 1.0f) || !(sigma_next_host[b] >= 0.0f && sigma_next_host[b] <= sigma_host[b]))
+            return fail(SDV2_INVALID_ARG, "stream %d: need 0 <= sigma_next <= sigma <= 1", b);
+        if (sigma_next_host[b] > 0.0f && !eps_next_dev) return fail(SDV2_INVALID_ARG, "stream %d has a further step but eps_next is null", b);
+    }
+    HIP_TRY(launch_sampler(z_dev, v_dev, eps_next_dev, z_next_dev, x0_dev, B, elems_per_stream, sigma_host, sigma_next_host,
+                           static_cast<hipStream_t>(hip_stream)), "sampler kernel");
+    return SDV2_OK;
+}
+
+size_t sdv2_denoise_latents_workspace_bytes(const sdv2_model_cfg* cfg, int32_t B, int32_t L) {
+    const size_t dn = sdv2_denoise_workspace_bytes(cfg, B, L);
+    const size_t io = sdv2_latent_io_workspace_bytes(cfg, B, L);
+    if (!dn || !io) return 0;
+    const size_t rows = (size_t)B * L;
+    return dn + io + align_up(rows * cfg->C * 4, 256) + align_up((size_t)B * cfg->C * 4, 256) + align_up(rows * kPatchWidth * 4, 256);
+}
+
+int32_t sdv2_denoise_latents_step(const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, const sdv2_io_weights* io,
+                                  sdv2_kv_cache* cache, float* z_dev, const float* eps_next_dev, float* x0_dev,
+                                  const float* sigma_host, const float* sigma_next_host, const void* const* kt_dev,
+                                  const void* const* vtt_dev, const sdv2_chunk_desc* chunks, int32_t B, void* workspace_dev,
+                                  size_t workspace_bytes, void* hip_stream) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!io_weights_ok(io)) return fail(SDV2_INVALID_ARG, "bad io weights");
+    if (!z_dev || !sigma_host || !sigma_next_host || !chunks || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    if (B <= 0 || B > SDV2_MAX_BATCH) return fail(SDV2_INVALID_ARG, "B = %d out of range", B);
+    float ts[SDV2_MAX_BATCH];
+    for (int b = 0; b < B; ++b) {
+        if (!(sigma_host[b] > 0.0f && sigma_host[b] <= 1.0f) || !(sigma_next_host[b] >= 0.0f && sigma_next_host[b] <= sigma_host[b]))
+            return fail(SDV2_INVALID_ARG, "stream %d: need 0 <= sigma_next <= sigma, 0 < sigma <= 1", b);
+        if (sigma_next_host[b] > 0.0f && !eps_next_dev) return fail(SDV2_INVALID_ARG, "stream %d has a further step but eps_next is null", b);
+        if (chunks[b].n_frames != chunks[0].n_frames || chunks[b].n_frames <= 0) return fail(SDV2_INVALID_ARG, "n_frames must be positive and equal across streams");
+        ts[b] = 1000.0f * sigma_host[b];
+    }
+    const int F = chunks[0].n_frames, L = F * cfg->grid_h * cfg->grid_w;
+    const size_t need = sdv2_denoise_latents_workspace_bytes(cfg, B, L);
+    if (!need || workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    const size_t rows = (size_t)B * L;
+    unsigned char* p = static_cast<unsigned char*>(workspace_dev);
+    const size_t dn = sdv2_denoise_workspace_bytes(cfg, B, L), iob = sdv2_latent_io_workspace_bytes(cfg, B, L);
+    void* dn_ws = p;
+    void* io_ws = p + dn;
+    float* x = reinterpret_cast<float*>(p + dn + iob);
+    float* tvec = reinterpret_cast<float*>(p + dn + iob + align_up(rows * cfg->C * 4, 256));
+    float* v = reinterpret_cast<float*>(p + dn + iob + align_up(rows * cfg->C * 4, 256) + align_up((size_t)B * cfg->C * 4, 256));
+    // the cache-touching call comes first among the ones that can still refuse, so that a refusal leaves everything as it was
+    int32_t rc = sdv2_timestep_vector(cfg, mw, B, ts, tvec, dn_ws, dn, hip_stream);
+    if (rc) return rc;
+    rc = sdv2_patch_embed(cfg, io, z_dev, B, F, x, io_ws, iob, hip_stream);
+    if (rc) return rc;
+    rc = sdv2_denoise_step(cfg, mw, cache, x, nullptr, tvec, kt_dev, vtt_dev, chunks, B, dn_ws, dn, hip_stream);
+    if (rc) return rc;
+    rc = sdv2_output_head(cfg, io, x, tvec, B, F, v, io_ws, iob, hip_stream);
+    if (rc) return rc;
+    return sdv2_sampler_update(z_dev, v, eps_next_dev, z_dev, x0_dev, B, (int64_t)kLatentChannels * F * 4 * cfg->grid_h * cfg->grid_w,
+                               sigma_host, sigma_next_host, hip_stream);
+}
+
+}  // extern "C"
+
 // ------------------------------------------------------------------------------------------ stream batch over denoising steps
 struct sdv2_stream_batch {
     int n_steps, n_frames;

@@ -16,6 +16,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr int kHeadDim = 128;
 constexpr int kMaxBatch = 8;
+constexpr int kLatentChannels = 16;      // VAE latent channels; a token covers 2 x 2 latent positions (64 numbers)
 
 // Column of a V^T cache row that holds slot s: inside every group of 16 slots the two middle groups of four
 // trade places (0-3, 8-11, 4-7, 12-15), the order in which the S^T accumulator of the attention kernel holds
@@ -227,6 +228,14 @@ hipError_t launch_set_step_desc(const StepDesc& d, StepDesc* dst, hipStream_t s)
 // used once before a stream capture so that no attribute call falls inside it.
 void set_attributes_only(bool on);
 bool attributes_only();
+
+// Latents <-> tokens, noise rate, sampler update (latent_io.hip).  z, v: fp32 [B][16][F][2 gh][2 gw]; patches bf16 and
+// tok fp32 [B F gh gw][64]; n = elements per stream; rate / sigma / sigma_next: host arrays [B].
+hipError_t launch_patchify(const float* z, bf16* patches, int B, int F, int gh, int gw, hipStream_t s);
+hipError_t launch_unpatchify(const float* tok, float* v, int B, int F, int gh, int gw, hipStream_t s);
+hipError_t launch_noise(const float* x, const float* eps, float* out, int B, long long n, const float* rate, hipStream_t s);
+hipError_t launch_sampler(const float* z, const float* v, const float* eps, float* z_next, float* x0, int B, long long n,
+                          const float* sigma, const float* sigma_next, hipStream_t s);
 
 // Benchmark-only microkernels: a register-resident loop of bf16 matrix instructions (iters x 8 per wave, eight waves
 // per workgroup) and a streaming copy of `bytes` (multiple of 16) bytes.

@@ -88,6 +88,26 @@ class DeviceModel:
         binding.denoise_step(self.cfg, self.mw, self.cache, x, kt, vtt, binding.chunk_descs(descs),
                              self.workspace(B, L), timesteps=timesteps, tvec=tvec)
 
+    def io(self, base_seed=0):
+        """Patch-embedding and output-head weights in HBM and the struct that points at them (made on first use)."""
+        if not hasattr(self, "_io"):
+            self.io_t = {k: v.to(self.device) for k, v in wk.io_weights(self.wl, base_seed).items()}
+            self._io = binding.io_weights(self.io_t)
+        return self._io
+
+    def denoise_latents(self, z, descs, sigmas, sigmas_next, eps_next=None, x0=None):
+        """z: fp32 [B, 16, F, 2 grid_h, 2 grid_w] device tensor, updated in place to the next step's input."""
+        B, L = z.shape[0], z.shape[2] * self.wl.grid_h * self.wl.grid_w
+        pick = lambda d: min(max(d[0], 0), self.n_streams - 1)     # bad ids still reach the library
+        kt = binding.ptr_array([self.kt[layer][pick(d)] for layer in range(self.N) for d in descs])
+        vtt = binding.ptr_array([self.vtt[layer][pick(d)] for layer in range(self.N) for d in descs])
+        key = ("latents", B, L)
+        if key not in self._ws:
+            self._ws[key] = torch.empty(binding.denoise_latents_workspace_bytes(self.cfg, B, L), dtype=torch.uint8,
+                                        device=self.device)
+        binding.denoise_latents_step(self.cfg, self.mw, self.io(), self.cache, z, eps_next, x0, sigmas, sigmas_next,
+                                     kt, vtt, binding.chunk_descs(descs), self._ws[key])
+
     def graph(self, x, stream_ids, n_frames):
         """Records sdv2_denoise_step on the fp32 [B, L, C] tensor x for these streams; returns the handle (the
         workspace and the descriptor buffer stay alive in this object)."""
