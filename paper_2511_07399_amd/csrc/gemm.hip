@@ -669,6 +669,185 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles
     run_epilogue<TM, TN>(g, acc, stage, m0 + wm * (32 * TM), n0 + wn * (32 * TN), lane);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Alternating kernel for shapes that fill the chip with 256 x 256 tiles.  The eight waves work as two groups of
+// four (one wave of each group on every SIMD) that run half a step apart.  A step of a wave is a memory phase (all
+// fragment reads of the step, its share of the direct loads, then the waits) and a matrix phase (nothing but the
+// step's 16 MFMAs), each closed by a workgroup barrier; group 1 takes one extra barrier before its first step and
+// group 0 one after its last, so while one wave of a SIMD issues MFMAs back to back the other one reads LDS and
+// waits, and the matrix pipe does not drain at a barrier that both of its waves reach together.
+//   Rows are fetched in whole 128-byte lines (k tiles of 64).  A stage of 64 k is 64 KB and the LDS holds two and a
+// half, so the ring is kept in half stages of 32 KB: unit 2t = the 256 rows of A for k tile t, unit 2t + 1 = the
+// 256 rows of W, unit u in slot u % 5.  A step is half a k tile (two MFMA k steps); step 2t + h reads its fragments
+// from the slots of units 2t and 2t + 1 at column half h and issues the loads of unit 2t + h + 3 into the slot that
+// unit 2t + h - 2 left.
+//   Barrier j (counted after the prologue's) closes the memory phase of step c for group 0 when j = 2c + 1, for
+//   group 1 when j = 2c + 2.  Units 2t + 2 and 2t + 3 are first read in step 2t + 2, i.e. after barrier 4t + 4;
+//   every wave waits for its own loads of both at the end of its memory phase of step 2t + 1 (only the loads of
+//   unit 2t + 4 may still be in flight), i.e. before barrier 4t + 4 at the latest.  The slot of unit u - 5 was last
+//   read in the memory phase of step u - 4 or u - 5 (the odd step of its tile) by group 1, which waits for its
+//   fragments before the barrier that closes that phase; the loads of unit u are issued in step u - 3, after it.
+//   Measured with s_memtime on one wave of each group (8192^3, clocks per step of 32 k; the step's MFMAs alone
+// are 1030 per SIMD): fragment reads 250, direct loads 400, waits and barrier 100 = a memory phase of 750 against
+// a matrix phase of 515, so a step takes 2 x 750.  What fills the memory phase is the LDS pipeline: about 5 clocks per
+// ds_read_b128 of a wave and 25 per direct load (13 for a ds_write_b128 of the same kilobyte), whichever order the
+// two are issued in and however far ahead the loads run (neither the latency of the loads nor the L2 is the limit:
+// the same clocks per step with 16 workgroups and with 256, where the core clock drops from 2.4 to 1.8 GHz).
+template <int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(512, 1) void gemm_alt64_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m,
+                                                             int splitk) {
+    static_assert(WM * WN == 8 && 32 * TM * WM == 256 && 32 * TN * WN == 256, "eight waves, 256 x 256 tiles");
+    constexpr int NW = 8, BK = 64, SLOTS = 5, LPW = 4;
+    constexpr int BM = 256;
+    constexpr int UNIT_BYTES = 256 * BK * 2;         // 32 KB
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN;
+    const int wn = wave % WN;
+    const int l31 = lane & 31;
+    const int lh = lane >> 5;
+
+    const int nwg = gridDim.x;
+    const int logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
+    const int tiles = tiles_m * tiles_n;
+    if (logical >= tiles * splitk) return;
+    const int ks = logical / tiles;                              // which part of k (0 when k is not split)
+    const int t_id = logical - ks * tiles;
+    const int group_size = group_m * tiles_n;
+    const int grp = t_id / group_size;
+    const int first_m = grp * group_m;
+    const int gm = min(tiles_m - first_m, group_m);
+    const int in_grp = t_id - grp * group_size;
+    const int tile_m = first_m + in_grp % gm;
+    const int tile_n = in_grp / gm;
+    const int m0 = tile_m * BM;
+    const int n0 = tile_n * 256;
+    const int nt_all = g.K / BK;
+    const int kt0 = (int)((long long)ks * nt_all / splitk);
+    const int nt = (int)((long long)(ks + 1) * nt_all / splitk) - kt0;
+    if (splitk > 1) {                                            // this part's fp32 partial sums, plain stores
+        g.out = g.splitk_partials + (size_t)ks * g.M * g.N;
+        g.epilogue = kEpiPartial;
+        g.bias = nullptr;
+    }
+
+    // A wave load fills 8 rows of 128 bytes; the lane that fills chunk position p of row r fetches logical chunk
+    // p ^ ((r / 2) % 8) of that row (the swizzle of gemm_dma_kernel).
+    uint32_t off_a[LPW], off_b[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int r = 8 * (wave + NW * i) + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        off_a[i] = (uint32_t)min(m0 + r, g.M - 1) * (uint32_t)g.K * 2u + (uint32_t)c * 16u;
+        off_b[i] = (uint32_t)min(n0 + r, g.N - 1) * (uint32_t)g.K * 2u + (uint32_t)c * 16u;
+    }
+    const unsigned char* a_base = reinterpret_cast<const unsigned char*>(g.a) + (size_t)kt0 * (BK * 2);
+    const unsigned char* w_base = reinterpret_cast<const unsigned char*>(g.w) + (size_t)kt0 * (BK * 2);
+    // the rows of A (of W) for k tile t, clamped (past the end the last tile is fetched again into a slot nobody reads)
+    auto issue_a = [&](int t, int slot) {
+        const unsigned char* src = a_base + (size_t)min(t, nt - 1) * (BK * 2);
+        unsigned char* dst = smem_raw + slot * UNIT_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) load_to_lds_b128(src + off_a[i], dst + i * (NW * 1024));
+    };
+    auto issue_b = [&](int t, int slot) {
+        const unsigned char* src = w_base + (size_t)min(t, nt - 1) * (BK * 2);
+        unsigned char* dst = smem_raw + slot * UNIT_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) load_to_lds_b128(src + off_b[i], dst + i * (NW * 1024));
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int a_row0 = wm * (32 * TM) + l31;
+    const int b_row0 = wn * (32 * TN) + l31;
+    const int key = (l31 >> 1) & 7;
+    bf16x8 fa[2][TM], fb[2][TN];
+    // fragments of the two MFMA k steps of column half h
+    auto read_half = [&](auto hc, int slot_a, int slot_b) {
+        constexpr int h = decltype(hc)::value;
+        const bf16* sa = reinterpret_cast<const bf16*>(smem_raw + slot_a * UNIT_BYTES);
+        const bf16* sb = reinterpret_cast<const bf16*>(smem_raw + slot_b * UNIT_BYTES);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int coff = ((2 * (2 * h + s2) + lh) ^ key) << 3;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[s2][i] = *reinterpret_cast<const bf16x8*>(sa + (a_row0 + 32 * i) * BK + coff);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[s2][j] = *reinterpret_cast<const bf16x8*>(sb + (b_row0 + 32 * j) * BK + coff);
+        }
+    };
+    auto mfma_half = [&]() {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s2][i], fb[s2][j], acc[i][j], 0, 0, 0);
+    };
+    auto barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    auto next = [](int slot, int by) { return slot + by >= SLOTS ? slot + by - SLOTS : slot + by; };
+
+    const std::integral_constant<int, 0> h0;
+    const std::integral_constant<int, 1> h1;
+    const bool second_group = wave >= NW / 2;        // wave-uniform (wave is in a scalar register)
+    issue_a(0, 0);
+    issue_b(0, 1);
+    issue_a(1, 2);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPW));      // units 0 and 1 have landed
+    barrier();
+    if (second_group) barrier();
+    int sa = 0, sb = 1, sl = 3;                      // slots of A and W of tile t, slot of the next unit to load
+    for (int t = 0; t < nt; ++t) {
+        // ---- step 2t, memory phase: fragments of the first column half, loads of unit 2t + 3 (W of tile t + 1)
+        __builtin_amdgcn_sched_barrier(0);
+        read_half(h0, sa, sb);
+        issue_b(t + 1, sl);
+        sl = next(sl, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // the fragments are in registers (lgkmcnt 0, no wait on loads)
+        barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half();
+        __builtin_amdgcn_sched_barrier(0);
+        barrier();
+        // ---- step 2t + 1: second column half, loads of unit 2t + 4 (A of tile t + 2); tile t + 1 has landed
+        __builtin_amdgcn_sched_barrier(0);
+        read_half(h1, sa, sb);
+        issue_a(t + 2, sl);
+        sl = next(sl, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPW) & 0xF0FF);
+        barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half();
+        __builtin_amdgcn_sched_barrier(0);
+        barrier();
+        sa = next(sa, 2);
+        sb = next(sb, 2);
+    }
+    if (!second_group) barrier();
+
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    float* stage = reinterpret_cast<float*>(smem_raw) + wave * EPI_WAVE_FLOATS;
+    run_epilogue<TM, TN>(g, acc, stage, m0 + wm * (32 * TM), n0 + wn * (32 * TN), lane);
+}
+
 template <int WM, int WN, int TM, int TN>
 hipError_t launch_ring(const GemmArgs& g, int splitk, hipStream_t s) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
@@ -687,6 +866,24 @@ hipError_t launch_ring(const GemmArgs& g, int splitk, hipStream_t s) {
     // groups of four tile rows: an XCD's 32 concurrent tiles then cover 4 x 8 tiles, the shape with the fewest
     // distinct operand rows per k step
     hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 4, splitk);
+    return hipGetLastError();
+}
+
+template <int WM, int WN, int TM, int TN>
+hipError_t launch_alt64(const GemmArgs& g, int splitk, hipStream_t s) {
+    constexpr size_t smem = (size_t)5 * 256 * 64 * sizeof(bf16);      // five half stages: all 160 KB
+    static_assert(smem <= 160 * 1024 && smem >= (size_t)8 * EPI_WAVE_FLOATS * sizeof(float), "LDS");
+    const int tiles_m = (g.M + 255) / 256;
+    const int tiles_n = (g.N + 255) / 256;
+    const int grid = (tiles_m * tiles_n * splitk + 7) / 8 * 8;
+    static std::once_flag attr_once;          // one per instantiation
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&]() {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_alt64_kernel<WM, WN, TM, TN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    });
+    if (attr_err != hipSuccess || attributes_only()) return attr_err;
+    hipLaunchKernelGGL((gemm_alt64_kernel<WM, WN, TM, TN>), dim3(grid), dim3(512), smem, s, g, tiles_m, tiles_n, 4, splitk);
     return hipGetLastError();
 }
 
@@ -739,8 +936,9 @@ const TunedShape kTuned[] = {
 };
 
 // Otherwise: when 256 x 256 tiles fill at least 80 % of the compute units in every round, the direct-load
-// kernel with that tile wins (it moves the fewest bytes per flop through the L2, which is what bounds the
-// large shapes), in its ring variant (+2 to +15 % over the two-stage one on the shapes of the 14B block).  Else estimate the time of the busiest compute unit for the register-staged kernel: one k
+// kernel with that tile wins (it moves the fewest bytes per flop through the LDS and the L2), in its alternating
+// variant (+6 to +9 % over the ring variant on the batched 480p shapes, equal within 2 % on the 1024-row shapes of the
+// 14B block; the ring variant is +2 to +15 % over the two-stage one).  Else estimate the time of the busiest compute unit for the register-staged kernel: one k
 // tile of a workgroup costs a fixed part (~0.25 us alone, half of it when a second workgroup fills the
 // bubbles) plus ~21 ns per MFMA a wave issues (fitted to the sweep); small tiles fit two workgroups per unit.
 TilePlan plan_tiles(int M, int N, int K, int epilogue) {
@@ -751,7 +949,7 @@ TilePlan plan_tiles(int M, int N, int K, int epilogue) {
     {
         const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
         const long long rounds = (tiles + kCUs - 1) / kCUs;
-        if (K >= 512 && tiles * 10 >= rounds * kCUs * 8) return TilePlan{0, 0, 0, 6};
+        if (K >= 512 && tiles * 10 >= rounds * kCUs * 8) return TilePlan{0, 0, 0, 18};
     }
     TilePlan best{1, 4, 2};
     double best_cost = 1e300;
@@ -818,7 +1016,7 @@ hipError_t launch_tn(const GemmArgs& g, int tn, int splitk, hipStream_t s) {
 // chunk, where the tile count has to reach the number of compute units and a k iteration holds only a few matrix
 // instructions per wave: no staging registers and no LDS write instructions, three or four tiles in flight, and
 // two or three workgroups per compute unit to cover the barrier.
-constexpr int kDmaConfigs = 16;
+constexpr int kDmaConfigs = 18;
 hipError_t launch_dma_config(const GemmArgs& g, int id, int splitk, hipStream_t s) {
     switch (id) {
         case 1: return launch_dma<4, 2, 2, 4, 2>(g, splitk, s);      // 256 x 256, wave tile 64 x 128
@@ -837,6 +1035,8 @@ hipError_t launch_dma_config(const GemmArgs& g, int id, int splitk, hipStream_t 
         case 14: return launch_dma<4, 1, 1, 5, 3>(g, splitk, s);     // 128 x 160, three stages
         case 15: return launch_dma<4, 1, 1, 6, 3>(g, splitk, s);     // 128 x 192
         case 16: return launch_dma<4, 2, 1, 3, 3>(g, splitk, s);     // 128 x 192, eight waves of 32 x 96
+        case 17: return launch_alt64<4, 2, 2, 4>(g, splitk, s);      // 256 x 256, two wave groups half a step apart, ring of five half stages
+        case 18: return launch_alt64<2, 4, 4, 2>(g, splitk, s);
     }
     return hipErrorInvalidValue;
 }
@@ -1043,8 +1243,10 @@ void gemm_plan_name(int M, int N, int K, int epilogue, char* out, size_t cap) {
     static const int kDma[kDmaConfigs + 1][5] = {{0, 0, 0, 0, 0}, {4, 2, 2, 4, 2}, {2, 4, 4, 2, 2}, {2, 4, 2, 2, 3}, {4, 2, 2, 2, 3},
                                                  {4, 2, 2, 4, 0}, {2, 4, 4, 2, 0}, {4, 1, 1, 2, 3}, {4, 1, 1, 2, 4}, {4, 2, 1, 1, 4},
                                                  {2, 2, 1, 2, 4}, {2, 2, 2, 2, 3}, {2, 4, 2, 1, 3}, {4, 1, 1, 5, 2}, {4, 1, 1, 5, 3},
-                                                 {4, 1, 1, 6, 3}, {4, 2, 1, 3, 3}};
-    if (p.dma == 5 || p.dma == 6)
+                                                 {4, 1, 1, 6, 3}, {4, 2, 1, 3, 3}, {4, 2, 2, 4, 0}, {2, 4, 4, 2, 0}};
+    if (p.dma >= 17)
+        snprintf(out, cap, "gemm_alt64_kernel<%d, %d, %d, %d>", kDma[p.dma][0], kDma[p.dma][1], kDma[p.dma][2], kDma[p.dma][3]);
+    else if (p.dma == 5 || p.dma == 6)
         snprintf(out, cap, "gemm_ring_kernel<%d, %d, %d, %d>", kDma[p.dma][0], kDma[p.dma][1], kDma[p.dma][2], kDma[p.dma][3]);
     else if (p.dma)
         snprintf(out, cap, "gemm_dma_kernel<%d, %d, %d, %d, %d>", kDma[p.dma][0], kDma[p.dma][1], kDma[p.dma][2], kDma[p.dma][3],
@@ -1074,3 +1276,4 @@ size_t gemm_splitk_floats(int M, int N, int K, int epilogue) {
 }
 
 }  // namespace sdv2
+

@@ -61,6 +61,14 @@ GEMM_CASES = [
     (130, 256, 32 * 2, 0, "d5"),           # K = 64
     (520, 768, 1024, 2, "d6,3"),           # ring with three k parts (fp32 partial sums + reduce), gated residual
     (1000, 512, 640, 1, "d5,2"),           # ring, two k parts, GELU in the reduce pass, ragged M
+    (1000, 1536, 512, 1, "d17"),           # two wave groups half a step apart, half stages of 64 k; GELU, ragged M
+    (300, 640, 192, 2, "d18"),             # 3 k tiles, N not a multiple of the tile
+    (256, 256, 64, 3, "d18"),              # one k tile
+    (130, 256, 128, 0, "d17"),             # two k tiles
+    (520, 768, 1024, 2, "d18,3"),          # three k parts
+    (2048, 2048, 2048, 0, "d18"),          # 64 full tiles, 32 k tiles
+    (1024, 1024, 320, 0, "d17"),           # five k tiles: one turn of the slot ring
+    (1024, 1024, 384, 0, "d18"),           # six k tiles
     (300, 512, 1024, 2, "1,4,2,2"),        # k split in two parts + reduce kernel, gated residual, ragged M
     (260, 256, 2048, 3, "2,8,2,4"),        # four parts, residual
     (1024, 1536, 1536, 1, "1,5,2,3"),      # three parts, GELU in the reduce kernel, ragged N tile
