@@ -693,6 +693,11 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles
 // ds_read_b128 of a wave and 25 per direct load (13 for a ds_write_b128 of the same kilobyte), whichever order the
 // two are issued in and however far ahead the loads run (neither the latency of the loads nor the L2 is the limit:
 // the same clocks per step with 16 workgroups and with 256, where the core clock drops from 2.4 to 1.8 GHz).
+// Tried on this structure and dropped, all within the run-to-run spread of the figure above or worse: k tiles of 32
+// in four or five stages (same clocks per step); reads and loads interleaved three to one, or half of the waves
+// loading first (memory phase 740 to 770); the units staged through registers (global -> registers in the matrix
+// phase, ds_write_b128 in the memory phase: memory phase 680; with the writes in the matrix phase too the MFMA
+// wave stalls behind the other group's reads and a step grows by a fifth).
 template <int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(512, 1) void gemm_alt64_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m,
                                                              int splitk) {
