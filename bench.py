@@ -95,6 +95,7 @@ def main():
                 "roofline": m2["roofline"], "kernels": m2["kernels"]}
         also["graph_replay"] = measure_graph_replay(args.workload, args.steps, args.warmup)
         also["stream_batch"] = measure_stream_batch(args.workload) if args.workload == "wan1.3b-step" else None
+        also["latents"] = measure_latents(args.workload) if args.workload == "wan1.3b-step" else None
         also["refresh"] = measure_refresh(args.workload)
         also["motion"] = measure_motion()
 
@@ -494,6 +495,42 @@ def measure_stream_batch(workload, depths=(2, 4), steps=12):
         torch.cuda.empty_cache()
     return {"workload": "%s, one stream, n denoising steps per chunk as n batch rows at n noise depths (own cache per "
                         "depth), steady state, %d timed micro-steps" % (base.name, steps), "depths": out}
+
+
+def measure_latents(workload, steps=10):
+    """The same step with latents in and latents out (sdv2_denoise_latents_step: timestep vector, patch embedding, the
+    blocks, output head, sampler update) beside the hidden-state step the headline times: what the steps around the
+    blocks add.  Cache at steady state, one stream, one denoising step per chunk."""
+    import torch
+    from paper_2511_07399_amd import workloads as wk
+    from paper_2511_07399_amd.runner import DeviceModel
+    wl = wk.WORKLOADS[workload]
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    gpu = DeviceModel(wl, base_seed=0, device=dev, weight_device=dev, n_streams=1)
+    gpu.io()
+    zs = [wk.latent_chunk(wl, c, 0, device=dev).unsqueeze(0).contiguous() for c in range(4)]
+    eps = wk.latent_chunk(wl, 0, 0, device=dev, kind=1).unsqueeze(0).contiguous()
+    z = torch.empty_like(zs[0])
+    fill = (wl.sink_frames + wl.window_frames) // wl.frames_per_chunk + 3
+    c = 0
+    for _ in range(fill):
+        z.copy_(zs[c % 4])
+        gpu.denoise_latents(z, [(0, c * wl.frames_per_chunk, wl.frames_per_chunk, 1)], [0.75], [0.5], eps_next=eps)
+        c += 1
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        gpu.denoise_latents(z, [(0, c * wl.frames_per_chunk, wl.frames_per_chunk, 1)], [0.75], [0.5], eps_next=eps)
+        c += 1
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(z).all())
+    ms = ev0.elapsed_time(ev1) / steps
+    gpu.close()
+    return {"ms_per_step_latents_in_latents_out": round(ms, 4),
+            "latent_shape": list(zs[0].shape[1:]), "entry_point": "sdv2_denoise_latents_step"}
 
 
 def measure_refresh(workload, reps=20):
