@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
     // Half of S^T of the tile in stage sk: d steps 4 half .. 4 half + 3 of both 32-key blocks.  The eight K
     // fragments are read first, the MFMAs alternate between the two accumulators (a dependent MFMA would
     // wait 12 clocks longer for its predecessor).
-    auto qk_half = [&](f32x16 (&s)[2], const unsigned char* sk, int half) {
+    auto qk_half = [&](f32x16 (&s)[2], const unsigned char* sk, int half, auto&& after_reads) {
         if (half == 0) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -178,12 +178,14 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
             for (int kb = 0; kb < 2; ++kb)
                 kf[i][kb] = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + l31) * 256 +
                                                              (((2 * (4 * half + i) + lh) ^ (l31 & 15)) << 4));
+        after_reads();
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i][kb], qf[4 * half + i], s[kb], 0, 0, 0);
     };
+    auto nothing = []() {};
 
     auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };       // vmcnt(0) only
     auto barrier = [&]() {
@@ -204,8 +206,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
             blank_v_tail(t, rel & 1);
             __syncthreads();
         }
-        if (t + 2 < t1) load_k(t + 2, rel & 1);
-        if (t + 1 < t1) load_v(t + 1, (rel + 1) & 1);
         const unsigned char* sk = k_stage + ((rel + 1) & 1) * K_TILE_BYTES;
         const unsigned char* sv = v_stage + (rel & 1) * V_TILE_BYTES;
 
@@ -219,8 +219,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
         // ---- first half of S^T(t+1) on the matrix unit | row maximum of tile t on the vector unit.  (Past the
         // last tile this reads a stale stage and the result is dropped: no branch, so that matrix and vector
         // instructions share a basic block and can be interleaved.)
+        // The loads of K(t+2) and V(t+1) go out between these MFMAs, one each: issued in a burst after the barrier they
+        // hold every wave of the unit (an issuing wave waits while the LDS pipeline takes in the loads before its own,
+        // about 25 clocks each) with the matrix pipe idle.  They are unconditional: past the last tile they fetch it
+        // again into a stage that nobody reads, so that matrix, vector and load instructions share a basic block.
         __builtin_amdgcn_sched_barrier(0);
-        qk_half(s_nxt, sk, 0);
+        qk_half(s_nxt, sk, 0, [&]() {
+            load_k(min(t + 2, t1 - 1), rel & 1);
+            load_v(min(t + 1, t1 - 1), (rel + 1) & 1);
+        });
         // four independent chains (a dependent vector instruction waits about twice as long as an independent one)
         float mc[4];
 #pragma unroll
@@ -233,10 +240,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
         float mx = max2_f32(max3_f32(mc[0], mc[1], mc[2]), mc[3]);
         mx = max_xor32(mx);
         const float m_new = fmaxf(m_run, mx * scale_log2e);     // finite: every tile has a valid key
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);       // the eight fragment reads, then MFMA | vector work
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);       // the eight fragment reads, then MFMA | load | vector work
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (m < 2 * LPT) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
         }
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // rescale only when some row's maximum moved
@@ -250,7 +258,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
         }
         // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
         __builtin_amdgcn_sched_barrier(0);
-        qk_half(s_nxt, sk, 1);
+        qk_half(s_nxt, sk, 1, nothing);
         float ls[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         bf16x8 pf[4];
 #pragma unroll
@@ -300,8 +308,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
         if (t0 + 1 < t1) load_k(t0 + 1, 1);
         wait_loads();
         barrier();
-        qk_half(s_a, k_stage, 0);
-        qk_half(s_a, k_stage, 1);
+        qk_half(s_a, k_stage, 0, nothing);
+        qk_half(s_a, k_stage, 1, nothing);
     }
     // full tiles in pairs (the two S^T register sets trade places), then what is left: at most one full tile
     // and the tail tile
