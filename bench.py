@@ -154,8 +154,19 @@ def measure_peaks():
     copy = best(lambda: 2 * binding.prof_peak_copy(src, dst))
     assert torch.equal(src[:4096], dst[:4096]) and torch.equal(src[-4096:], dst[-4096:])
     del src, dst, sink
+    # the LDS pipeline of one compute unit: shader clocks per wave instruction that moves 1 KB
+    lds_iters = 2000
+    scratch = torch.zeros(40960 // 8, dtype=torch.int64, device=dev)
+    binding.prof_lds_rates(lds_iters, scratch)
+    binding.prof_lds_rates(lds_iters, scratch)
+    torch.cuda.synchronize()
+    ticks = [int(t) for t in scratch[:3].cpu()]
+    lds = {n: round(t / (lds_iters * 8 * 8.0), 2) for n, t in zip(("ds_read_b128", "ds_write_b128", "direct global->LDS load x4"), ticks)}
+    del scratch
     torch.cuda.empty_cache()
     return {
+        "lds_clocks_per_wave_instruction_of_1KB": dict(lds, how="one workgroup of eight waves issuing the same instruction "
+                                                       "back to back, s_memtime from first issue to last result"),
         "mfma_bf16": {"published": cm.MI355X_BF16_FLOPS / 1e12, "measured": round(mfma / 1e12, 1), "unit": "TFLOP/s",
                       "how": "v_mfma_f32_32x32x16_bf16 on register operands, 8 independent accumulators per wave, "
                              "8 waves per workgroup, %d workgroups x %d iterations" % (wgs, iters)},

@@ -552,6 +552,11 @@ int32_t sdv2_prof_end(int32_t* tags_out, float* ms_out, int32_t capacity, int32_
  * sdv2_prof_peak_copy: dst <- src, `bytes` (multiple of 16) bytes, 16-byte accesses, grid-stride; moves 2 x bytes
  *   through HBM when the buffers exceed the caches.
  * Both only enqueue one kernel; the caller times it with events on the same stream.
+ * sdv2_prof_lds_rates: three launches of one workgroup of eight waves, each wave issuing iters x 8 times the same LDS
+ *   instruction of 16 bytes per lane (1 KB per wave instruction): ds_read_b128, ds_write_b128, and the direct
+ *   global -> LDS load; the shader clocks each took (s_memtime, first instruction to last result) are left as three
+ *   uint64 at the start of scratch_dev (dev, 256-byte aligned, >= 40960 bytes, contents overwritten; the direct loads
+ *   read its bytes 8192 .. 40959).  Clocks per wave instruction = ticks / (iters * 8 * 8).  Enqueue only.
  * ------------------------------------------------------------------------------------------------ */
 /* sdv2_prof_kernel_name: the kernel instantiation the library's planner picks, spelled as a profiler prints it, so
  * that the benchmark can group launch sites by kernel the way a rocprofv3 summary does.
@@ -562,6 +567,7 @@ int32_t sdv2_prof_kernel_name(int32_t kind, int32_t B, int32_t L, int32_t a0, in
 int32_t sdv2_prof_peak_mfma(int32_t iters, int32_t workgroups, float* sink_dev, size_t sink_floats, double* flops_out,
                             void* hip_stream);
 int32_t sdv2_prof_peak_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
+int32_t sdv2_prof_lds_rates(int32_t iters, void* scratch_dev, size_t scratch_bytes, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Tuning hook for tests and sweeps (not for production use, not thread safe): replaces the library's own choice of

@@ -79,7 +79,7 @@ EXPORTS = (
     "sdv2_conditioning_workspace_bytes", "sdv2_conditioning", "sdv2_block_workspace_bytes",
     "sdv2_dit_block_forward", "sdv2_denoise_workspace_bytes", "sdv2_denoise_step", "sdv2_gemm_workspace_bytes", "sdv2_gemm_bf16",
     "sdv2_attention_workspace_bytes", "sdv2_attention_bf16", "sdv2_prof_begin", "sdv2_prof_end",
-    "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_prof_kernel_name", "sdv2_tuning_set", "sdv2_gemm_noalloc_max_scratch_bytes",
+    "sdv2_prof_peak_mfma", "sdv2_prof_peak_copy", "sdv2_prof_lds_rates", "sdv2_prof_kernel_name", "sdv2_tuning_set", "sdv2_gemm_noalloc_max_scratch_bytes",
     "sdv2_gemm_bf16_noalloc", "sdv2_stream_batch_rows_bytes", "sdv2_stream_batch_create", "sdv2_stream_batch_destroy",
     "sdv2_stream_batch_reset", "sdv2_stream_batch_step", "sdv2_denoise_graph_state_bytes", "sdv2_denoise_graph_create",
     "sdv2_denoise_graph_launch", "sdv2_denoise_graph_destroy", "sdv2_timestep_vector", "sdv2_latent_io_workspace_bytes",
@@ -156,6 +156,7 @@ def load_library():
     lib.sdv2_prof_end.argtypes = [C.POINTER(i32), C.POINTER(C.c_float), i32, C.POINTER(i32)]
     lib.sdv2_prof_peak_mfma.argtypes = [i32, i32, f32p, sz, C.POINTER(C.c_double), vp]
     lib.sdv2_prof_peak_copy.argtypes = [vp, vp, sz, vp]
+    lib.sdv2_prof_lds_rates.argtypes = [i32, vp, sz, vp]
     lib.sdv2_tuning_set.argtypes = [C.c_char_p, C.c_char_p]
     lib.sdv2_prof_kernel_name.argtypes = [i32, i32, i32, i32, i32, i32, C.c_char_p, sz]
     lib.sdv2_gemm_noalloc_max_scratch_bytes.restype = sz
@@ -522,6 +523,12 @@ def prof_peak_copy(src, dst):
     assert dst.numel() * dst.element_size() == n
     _check(_lib.sdv2_prof_peak_copy(_ptr(src), _ptr(dst), n, _stream()))
     return n
+
+
+def prof_lds_rates(iters, scratch):
+    """Enqueues the three LDS-rate launches; the three tick counts are the first three int64 of ``scratch``."""
+    load_library()
+    _check(_lib.sdv2_prof_lds_rates(iters, _ptr(scratch), scratch.numel() * scratch.element_size(), _stream()))
 
 
 def prof_kernel_name(kind, B, L, a0, a1, a2):

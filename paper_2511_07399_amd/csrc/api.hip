@@ -1721,6 +1721,17 @@ int32_t sdv2_prof_peak_copy(const void* src_dev, void* dst_dev, size_t bytes, vo
     return SDV2_OK;
 }
 
+int32_t sdv2_prof_lds_rates(int32_t iters, void* scratch_dev, size_t scratch_bytes, void* hip_stream) {
+    if (iters <= 0 || iters > (1 << 20)) return fail(SDV2_INVALID_ARG, "iters = %d out of range", iters);
+    if (!scratch_dev || scratch_bytes < 40960) return fail(SDV2_INVALID_ARG, "scratch is null or below 40960 bytes");
+    if (reinterpret_cast<uintptr_t>(scratch_dev) % 256) return fail(SDV2_INVALID_ARG, "scratch must be 256-byte aligned");
+    unsigned char* p = static_cast<unsigned char*>(scratch_dev);
+    // [0, 32) three tick counts; [2048, 4096) sink; [8192, 40960) the 32 KB the direct loads read
+    HIP_TRY(launch_peak_lds(iters, p + 8192, reinterpret_cast<float*>(p + 2048), reinterpret_cast<unsigned long long*>(p),
+                            static_cast<hipStream_t>(hip_stream)), "LDS rate kernels");
+    return SDV2_OK;
+}
+
 int32_t sdv2_prof_kernel_name(int32_t kind, int32_t B, int32_t L, int32_t a0, int32_t a1, int32_t a2, char* out,
                               size_t capacity) {
     if (!out || capacity < 8) return fail(SDV2_INVALID_ARG, "out is null or too small");

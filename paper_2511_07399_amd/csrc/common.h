@@ -242,5 +242,6 @@ hipError_t launch_sampler(const float* z, const float* v, const float* eps, floa
 hipError_t launch_peak_mfma(int iters, int workgroups, float* sink, hipStream_t s);
 double peak_mfma_flops(int iters, int workgroups);
 hipError_t launch_peak_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+hipError_t launch_peak_lds(int iters, const unsigned char* src, float* sink, unsigned long long* ticks, hipStream_t s);
 
 }  // namespace sdv2

@@ -690,7 +690,8 @@ __global__ __launch_bounds__(512, 1) void gemm_ring_kernel(GemmArgs g, int tiles
 //   Measured with s_memtime on one wave of each group (8192^3, clocks per step of 32 k; the step's MFMAs alone
 // are 1030 per SIMD): fragment reads 250, direct loads 400, waits and barrier 100 = a memory phase of 750 against
 // a matrix phase of 515, so a step takes 2 x 750.  What fills the memory phase is the LDS pipeline: about 5 clocks per
-// ds_read_b128 of a wave and 25 per direct load (13 for a ds_write_b128 of the same kilobyte), whichever order the
+// ds_read_b128 of a wave and 25 per direct load here (alone on a compute unit a kilobyte takes 4.6 clocks to read,
+// 16 to load directly and 13 to write with ds_write_b128: the rate microkernel of peaks.hip), whichever order the
 // two are issued in and however far ahead the loads run (neither the latency of the loads nor the L2 is the limit:
 // the same clocks per step with 16 workgroups and with 256, where the core clock drops from 2.4 to 1.8 GHz).
 // Tried on this structure and dropped, all within the run-to-run spread of the figure above or worse: k tiles of 32

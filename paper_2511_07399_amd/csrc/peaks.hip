@@ -48,7 +48,47 @@ __global__ __launch_bounds__(256) void peak_copy_kernel(const f32x4* __restrict_
     for (; i < n16; i += stride) dst[i] = src[i];
 }
 
+// What the LDS pipeline of a compute unit takes per wave instruction that moves a kilobyte (64 lanes x 16 bytes):
+// the eight waves of one workgroup issue the same instruction back to back, `iters` rounds of eight, and wave 0 writes
+// the shader clocks from the first to the last into ticks[mode].  mode 0: ds_read_b128; 1: ds_write_b128; 2: direct
+// global -> LDS load of 16 bytes per lane (global_load_lds_dwordx4) from a 32 KB buffer that stays in the caches.
+typedef __attribute__((address_space(3))) void* lds_void_ptr_t;
+template <int MODE>
+__global__ __launch_bounds__(512, 1) void peak_lds_kernel(int iters, const unsigned char* src, float* sink,
+                                                           unsigned long long* ticks) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[65536];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    unsigned char* base = lds + wave * 8192;
+    f32x4 v = {1.0f * lane, 2.0f, 3.0f, 4.0f};
+    for (int i = threadIdx.x; i < 65536 / 16; i += 512) reinterpret_cast<f32x4*>(lds)[i] = v;
+    __syncthreads();
+    const unsigned long long t0 = __builtin_amdgcn_s_memtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (MODE == 0) v += *reinterpret_cast<const f32x4*>(base + u * 1024 + lane * 16);
+            else if (MODE == 1) *reinterpret_cast<f32x4*>(base + u * 1024 + lane * 16) = v;
+            else __builtin_amdgcn_global_load_lds(src + ((wave * 8 + u) & 31) * 1024 + lane * 16, (lds_void_ptr_t)(base + u * 1024), 16, 0, 0);
+        }
+        asm volatile("" ::: "memory");                 // the eight of a round stay eight: no merging across rounds
+        if (MODE == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);      // at most one round of loads in flight behind this one
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);                // everything has landed (vmcnt 0, lgkmcnt 0)
+    __syncthreads();
+    const unsigned long long t1 = __builtin_amdgcn_s_memtime();
+    sink[threadIdx.x] = v[0] + v[1] + v[2] + v[3] + reinterpret_cast<const float*>(lds)[threadIdx.x];
+    if (threadIdx.x == 0) ticks[MODE] = t1 - t0;
+}
+
 }  // namespace
+
+hipError_t launch_peak_lds(int iters, const unsigned char* src, float* sink, unsigned long long* ticks, hipStream_t s) {
+    hipLaunchKernelGGL(peak_lds_kernel<0>, dim3(1), dim3(512), 0, s, iters, src, sink, ticks);
+    hipLaunchKernelGGL(peak_lds_kernel<1>, dim3(1), dim3(512), 0, s, iters, src, sink, ticks);
+    hipLaunchKernelGGL(peak_lds_kernel<2>, dim3(1), dim3(512), 0, s, iters, src, sink, ticks);
+    return hipGetLastError();
+}
 
 hipError_t launch_peak_mfma(int iters, int workgroups, float* sink, hipStream_t s) {
     hipLaunchKernelGGL(peak_mfma_kernel, dim3(workgroups), dim3(512), 0, s, iters, sink);

@@ -169,3 +169,31 @@ def test_stream_batch_handle_and_planner_hooks_on_the_host(lib):
             binding.tuning_set(name, value)
         assert e.value.code == binding.INVALID_ARG
     assert binding.gemm_noalloc_max_scratch_bytes() == 32 << 20
+
+
+def test_latent_io_sizes_and_refusals_on_the_host(lib):
+    """Host-only parts of the latents-in / latents-out entry points: workspace sizes and the argument checks that
+    come before any launch (nothing here touches a GPU)."""
+    cfg = binding.model_cfg(512, 4, 2048, 8, 16, 64, 2)
+    L = 8 * 16
+    io_ws = binding.latent_io_workspace_bytes(cfg, 3, L)
+    assert io_ws >= 3 * L * 512 * 2 + 3 * L * 64 * 4 and io_ws % 256 == 0
+    assert binding.latent_io_workspace_bytes(cfg, 0, L) == 0 and binding.latent_io_workspace_bytes(cfg, 9, L) == 0
+    total = binding.denoise_latents_workspace_bytes(cfg, 3, L)
+    assert total >= binding.denoise_workspace_bytes(cfg, 3, L) + io_ws + 3 * L * 512 * 4
+    fake = C.c_void_p(0x100000)                                       # never dereferenced: every call below is refused
+    one = (C.c_float * 1)(0.5)
+    big = (C.c_float * 1)(1.5)
+    less = (C.c_float * 1)(0.25)
+    assert lib.sdv2_noise_latents(None, fake, fake, 1, 1024, one, None) == binding.INVALID_ARG
+    assert lib.sdv2_noise_latents(fake, fake, fake, 1, 1024, big, None) == binding.INVALID_ARG          # rate above 1
+    assert lib.sdv2_noise_latents(fake, fake, fake, 9, 1024, one, None) == binding.INVALID_ARG          # too many streams
+    assert lib.sdv2_sampler_update(fake, fake, fake, fake, None, 1, 1024, less, one, None) == binding.INVALID_ARG   # sigma grows
+    assert lib.sdv2_sampler_update(fake, fake, None, fake, None, 1, 1024, one, less, None) == binding.INVALID_ARG   # noise missing
+    assert lib.sdv2_sampler_update(fake, fake, fake, fake, None, 1, 0, one, less, None) == binding.INVALID_ARG
+    io = binding.IoWeights()                                          # struct_size 0, null pointers
+    assert lib.sdv2_patch_embed(C.byref(cfg), C.byref(io), fake, 1, 1, fake, fake, io_ws, None) == binding.INVALID_ARG
+    assert lib.sdv2_output_head(C.byref(cfg), C.byref(io), fake, fake, 1, 1, fake, fake, io_ws, None) == binding.INVALID_ARG
+    assert b"io weights" in lib.sdv2_last_error()
+    assert lib.sdv2_prof_lds_rates(100, None, 40960, None) == binding.INVALID_ARG
+    assert lib.sdv2_prof_lds_rates(100, fake, 1024, None) == binding.INVALID_ARG
