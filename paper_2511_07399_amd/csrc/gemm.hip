@@ -947,12 +947,18 @@ const TunedShape kTuned[] = {
 // 14B block; the ring variant is +2 to +15 % over the two-stage one).  Else estimate the time of the busiest compute unit for the register-staged kernel: one k
 // tile of a workgroup costs a fixed part (~0.25 us alone, half of it when a second workgroup fills the
 // bubbles) plus ~21 ns per MFMA a wave issues (fitted to the sweep); small tiles fit two workgroups per unit.
+// The direct-load kernels address an operand with 32-bit byte offsets per lane: they serve operands below 4 GiB.
+bool fits_32bit_offsets(int M, int N, int K) {
+    return (unsigned long long)M * K * 2 <= 0xFFFFFFFFull && (unsigned long long)N * K * 2 <= 0xFFFFFFFFull;
+}
+
 TilePlan plan_tiles(int M, int N, int K, int epilogue) {
     (void)epilogue;
+    const bool direct_ok = fits_32bit_offsets(M, N, K);
     for (const TunedShape& t : kTuned)
-        if (t.M == M && t.N == N && t.K == K) return t.plan;
+        if (t.M == M && t.N == N && t.K == K && (direct_ok || !t.plan.dma)) return t.plan;
     const int kCUs = 256;
-    {
+    if (direct_ok) {
         const long long tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
         const long long rounds = (tiles + kCUs - 1) / kCUs;
         if (K >= 512 && tiles * 10 >= rounds * kCUs * 8) return TilePlan{0, 0, 0, 18};
@@ -1024,6 +1030,7 @@ hipError_t launch_tn(const GemmArgs& g, int tn, int splitk, hipStream_t s) {
 // two or three workgroups per compute unit to cover the barrier.
 constexpr int kDmaConfigs = 18;
 hipError_t launch_dma_config(const GemmArgs& g, int id, int splitk, hipStream_t s) {
+    if (!fits_32bit_offsets(g.M, g.N, g.K)) return hipErrorInvalidValue;     // only reachable through the tuning override
     switch (id) {
         case 1: return launch_dma<4, 2, 2, 4, 2>(g, splitk, s);      // 256 x 256, wave tile 64 x 128
         case 2: return launch_dma<2, 4, 4, 2, 2>(g, splitk, s);      // 256 x 256, wave tile 128 x 64

@@ -156,6 +156,9 @@ def test_stream_batch_handle_and_planner_hooks_on_the_host(lib):
     # the planner's kernel names: large shapes take the 256 x 256 alternating kernel, the single-chunk attention of the 1.3B
     # block the key-split form, a capacity that is no multiple of 128 the one-key-stream form
     assert binding.prof_kernel_name("gemm", 4, 4680, 13824, 5120, 1).startswith("gemm_alt64_kernel<")
+    # an activation matrix of 4 GiB or more is beyond the 32-bit lane offsets of the direct-load kernels
+    assert binding.prof_kernel_name("gemm", 8, 40000, 8192, 8192, 0).startswith("gemm_kernel<")
+    assert binding.prof_kernel_name("gemm", 8, 30000, 8192, 8192, 0).startswith("gemm_alt64_kernel<")
     assert binding.prof_kernel_name("attention", 1, 1024, 12, 3072, 3072) == "attention_ks_kernel<2, 4>"
     assert binding.prof_kernel_name("attention", 1, 1024, 12, 3072, 3136).startswith("attention_kernel<")
     assert binding.prof_kernel_name("attention", 4, 4680, 40, 10920, 10944) == "attention_kernel<8>"
