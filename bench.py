@@ -500,9 +500,32 @@ def measure_stream_batch(workload, depths=(2, 4), steps=12):
             "ms_per_row": round(ms / n, 4), "finished_chunks_per_s": round(1e3 / ms, 1),
             "step_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "step_frac_mfma_peak": round(flops / (ms * 1e-3) / cm.MI355X_BF16_FLOPS, 4)}
+        # the same rotation with rows of latents (patch embedding, head and sampler update inside every micro-step)
+        binding.stream_batch_reset(sb)
+        for layer_stream in range(n):
+            binding.kv_cache_reset(gpu.cache, layer_stream)
+        io = gpu.io()
+        ws_l = torch.empty(binding.stream_batch_latents_workspace_bytes(gpu.cfg, n, wl.frames_per_chunk), dtype=torch.uint8, device=dev)
+        zs = [wk.latent_chunk(wl, c, 0, device=dev).contiguous() for c in range(4)]
+        eps = torch.stack([wk.latent_chunk(wl, 0, 0, device=dev, kind=2 + d) for d in range(n)]).contiguous()
+        z_out = torch.empty_like(zs[0])
+        sig = [1.0 - d / n for d in range(n + 1)]
+        m = 0
+        for _ in range(fill):
+            binding.stream_batch_latents_step(sb, gpu.cfg, gpu.mw, io, gpu.cache, zs[m % 4], m * wl.frames_per_chunk, sig, eps, kt, vtt, z_out, ws_l)
+            m += 1
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for _ in range(steps):
+            binding.stream_batch_latents_step(sb, gpu.cfg, gpu.mw, io, gpu.cache, zs[m % 4], m * wl.frames_per_chunk, sig, eps, kt, vtt, z_out, ws_l)
+            m += 1
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(z_out).all())
+        out["%d steps per chunk" % n]["ms_per_micro_step_rows_of_latents"] = round(ev0.elapsed_time(ev1) / steps, 4)
         binding.stream_batch_destroy(sb)
         gpu.close()
-        del gpu, rows, ws, xs
+        del gpu, rows, ws, xs, ws_l
         torch.cuda.empty_cache()
     return {"workload": "%s, one stream, n denoising steps per chunk as n batch rows at n noise depths (own cache per "
                         "depth), steady state, %d timed micro-steps" % (base.name, steps), "depths": out}

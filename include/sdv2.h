@@ -478,6 +478,27 @@ int32_t sdv2_denoise_latents_step(const sdv2_model_cfg* cfg, const sdv2_model_we
                                   const sdv2_chunk_desc* chunks, int32_t B,
                                   void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* The stream batch over denoising steps (Section 4.2) with rows of LATENTS at different noise levels, which is how the
+ * paper words it: the rotation of sdv2_stream_batch_step, each micro-step one batched sdv2_denoise_latents_step.
+ *   sigmas_host [n_steps + 1]: the noise levels, falling, sigmas_host[d] > 0 for d < n_steps; the row at depth d is
+ *     taken from sigmas_host[d] to sigmas_host[d + 1] (timestep 1000 sigmas_host[d]); with sigmas_host[n_steps] = 0
+ *     the chunk that leaves is the clean latent.
+ *   z_in_dev: the entering chunk's latent at level sigmas_host[0] (dev fp32 [16][F][2 grid_h][2 grid_w]; see
+ *     sdv2_noise_latents), or NULL when nothing enters.
+ *   eps_by_depth_dev: dev fp32 [n_steps] latents, entry d = the fresh noise for the chunk now at depth d (mixed in at
+ *     level sigmas_host[d + 1]; entries whose new level is 0 are not read); NULL allowed when every later level is 0.
+ *   z_out_dev: receives the leaving chunk's latent when *emitted_out = 1.
+ * The handle is the one of sdv2_stream_batch_create (its rows buffer is large enough for latents); one handle serves
+ * one kind of row until sdv2_stream_batch_reset (SDV2_BAD_STATE otherwise).  Workspace:
+ * sdv2_stream_batch_latents_workspace_bytes.  Errors as sdv2_stream_batch_step and sdv2_denoise_latents_step. */
+size_t sdv2_stream_batch_latents_workspace_bytes(const sdv2_model_cfg* cfg, int32_t n_steps, int32_t n_frames);
+int32_t sdv2_stream_batch_latents_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw,
+                                       const sdv2_io_weights* io, sdv2_kv_cache* cache, const float* z_in_dev,
+                                       int32_t frame_pos0, const float* sigmas_host, const float* eps_by_depth_dev,
+                                       const void* const* kt_dev, const void* const* vtt_dev, float* z_out_dev,
+                                       int32_t* emitted_out, int32_t* rows_out,
+                                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------------
  * The two dense kernels on their own (used by the per-kernel parity tests and the benchmark).
  *

@@ -84,7 +84,8 @@ EXPORTS = (
     "sdv2_stream_batch_reset", "sdv2_stream_batch_step", "sdv2_denoise_graph_state_bytes", "sdv2_denoise_graph_create",
     "sdv2_denoise_graph_launch", "sdv2_denoise_graph_destroy", "sdv2_timestep_vector", "sdv2_latent_io_workspace_bytes",
     "sdv2_patch_embed", "sdv2_output_head", "sdv2_noise_latents", "sdv2_sampler_update",
-    "sdv2_denoise_latents_workspace_bytes", "sdv2_denoise_latents_step",
+    "sdv2_denoise_latents_workspace_bytes", "sdv2_denoise_latents_step", "sdv2_stream_batch_latents_workspace_bytes",
+    "sdv2_stream_batch_latents_step",
 )
 
 LAUNCH_TAGS = ("adaLN-1", "QKV gemm", "rope+append", "self-attn", "out-proj gemm", "LN-3", "cross-q gemm",
@@ -187,6 +188,11 @@ def load_library():
     lib.sdv2_denoise_latents_step.argtypes = [C.POINTER(ModelCfg), C.POINTER(ModelWeights), C.POINTER(IoWeights), vp,
                                               f32p, f32p, f32p, fp, fp, C.POINTER(vp), C.POINTER(vp),
                                               C.POINTER(ChunkDesc), i32, vp, sz, vp]
+    lib.sdv2_stream_batch_latents_workspace_bytes.restype = sz
+    lib.sdv2_stream_batch_latents_workspace_bytes.argtypes = [C.POINTER(ModelCfg), i32, i32]
+    lib.sdv2_stream_batch_latents_step.argtypes = [vp, C.POINTER(ModelCfg), C.POINTER(ModelWeights), C.POINTER(IoWeights), vp,
+                                                   f32p, i32, fp, f32p, C.POINTER(vp), C.POINTER(vp), f32p,
+                                                   C.POINTER(i32), C.POINTER(i32), vp, sz, vp]
     _lib = lib
     return lib
 
@@ -681,3 +687,23 @@ def denoise_latents_step(cfg, mw, io, cache, z, eps_next, x0, sigmas, sigmas_nex
     _check(_lib.sdv2_denoise_latents_step(C.byref(cfg), C.byref(mw), C.byref(io), cache, _ptr(z), _ptr(eps_next),
                                           _ptr(x0), _timesteps(sigmas), _timesteps(sigmas_next), kt_array, vtt_array,
                                           chunks, len(chunks), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def stream_batch_latents_workspace_bytes(cfg, n_steps, n_frames):
+    load_library()
+    return int(_lib.sdv2_stream_batch_latents_workspace_bytes(C.byref(cfg), n_steps, n_frames))
+
+
+def stream_batch_latents_step(h, cfg, mw, io, cache, z_in, frame_pos0, sigmas, eps_by_depth, kt, vtt, z_out, workspace):
+    """One micro-step with rows of latents; returns (emitted, rows).  z_in: fp32 latent of the entering chunk or None;
+    sigmas: n_steps + 1 noise levels; eps_by_depth: fp32 [n_steps, 16, F, 2 grid_h, 2 grid_w] or None."""
+    if z_in is not None:
+        _dev(z_in, torch.float32)
+    if eps_by_depth is not None:
+        _dev(eps_by_depth, torch.float32)
+    _dev(z_out, torch.float32)
+    emitted, rows = C.c_int32(0), C.c_int32(0)
+    _check(_lib.sdv2_stream_batch_latents_step(h, C.byref(cfg), C.byref(mw), C.byref(io), cache, _ptr(z_in), frame_pos0,
+                                               _timesteps(sigmas), _ptr(eps_by_depth), kt, vtt, _ptr(z_out),
+                                               C.byref(emitted), C.byref(rows), _ptr(workspace), _nbytes(workspace), _stream()))
+    return bool(emitted.value), rows.value

@@ -1545,6 +1545,7 @@ struct sdv2_stream_batch {
     int32_t frame_pos0[SDV2_MAX_BATCH];
     int64_t entered;                   // chunks that have entered
     bool broken;
+    int mode;                          // 0: not used yet; 1: rows are hidden states; 2: rows are latents
 };
 
 extern "C" {
@@ -1587,6 +1588,7 @@ int32_t sdv2_stream_batch_create(const sdv2_model_cfg* cfg, int32_t n_steps, con
     }
     sb->entered = 0;
     sb->broken = false;
+    sb->mode = 0;
     *out = sb;
     return SDV2_OK;
 }
@@ -1601,40 +1603,35 @@ int32_t sdv2_stream_batch_reset(sdv2_stream_batch* sb) {
     for (int r = 0; r < SDV2_MAX_BATCH; ++r) sb->depth[r] = -1;
     sb->entered = 0;
     sb->broken = false;
+    sb->mode = 0;
     return SDV2_OK;
 }
 
-int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw,
-                               sdv2_kv_cache* cache, const float* x_in_dev, int32_t frame_pos0,
-                               const float* timesteps_host, const void* const* kt_dev, const void* const* vtt_dev,
-                               float* x_out_dev, int32_t* emitted_out, int32_t* rows_out, void* workspace_dev,
-                               size_t workspace_bytes, void* hip_stream) {
-    if (!sb) return fail(SDV2_INVALID_ARG, "handle is null");
-    if (sb->broken) return fail(SDV2_BAD_STATE, "an earlier micro-step failed half way: reset the pipeline and the caches");
-    const char* why;
-    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
-    if (!mw || !cache || !timesteps_host || !kt_dev || !vtt_dev || !x_out_dev || !emitted_out || !workspace_dev)
-        return fail(SDV2_INVALID_ARG, "null pointer");
-    if ((size_t)sb->n_frames * cfg->grid_h * cfg->grid_w * cfg->C != sb->row_floats)
-        return fail(SDV2_INVALID_ARG, "cfg differs from the one the pipeline was created with");
-    if (x_in_dev && frame_pos0 < 0) return fail(SDV2_INVALID_ARG, "frame_pos0 < 0");
+}  // extern "C"
+
+namespace {
+// One micro-step of the rotation for either kind of row.  io == nullptr: rows are hidden states [L, C] and level[d] is
+// the timestep of depth d.  Otherwise rows are latents [16, F, 2 grid_h, 2 grid_w], level[0 .. n] are the noise levels
+// (the row at depth d goes from level[d] to level[d + 1]) and eps_by_depth_dev[d] is the noise mixed into the row at
+// depth d at its new level; eps_rows_dev is workspace for the same noise in row order.
+int32_t stream_batch_step_impl(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw,
+                               const sdv2_io_weights* io, sdv2_kv_cache* cache, const float* in_dev, int32_t frame_pos0,
+                               const float* level, const float* eps_by_depth_dev, float* eps_rows_dev,
+                               const void* const* kt_dev, const void* const* vtt_dev, float* out_dev,
+                               int32_t* emitted_out, int32_t* rows_out, void* workspace_dev, size_t workspace_bytes,
+                               void* hip_stream) {
     const int n = sb->n_steps;
-    for (int d = 0; d < n; ++d)
-        if (sb->cache_ids[d] >= cache->cfg.n_streams) return fail(SDV2_INVALID_ARG, "cache stream %d of depth %d out of range", sb->cache_ids[d], d);
-    for (int layer = 0; layer < cfg->n_layers; ++layer)
-        if (!kt_dev[layer] || !vtt_dev[layer]) return fail(SDV2_INVALID_ARG, "text K/V of layer %d is null", layer);
     const int L = sb->n_frames * cfg->grid_h * cfg->grid_w;
-    const size_t need = sdv2_denoise_workspace_bytes(cfg, n, L);
-    if (workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    const size_t row_floats = io ? (size_t)4 * kLatentChannels * L : sb->row_floats;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const size_t row_bytes = sb->row_floats * sizeof(float);
+    const size_t row_bytes = row_floats * sizeof(float);
 
     // the entering chunk takes the row that the chunk emitted n micro-steps after it entered has left
     int new_row = -1;
-    if (x_in_dev) {
+    if (in_dev) {
         new_row = (int)(sb->entered % n);
         if (sb->depth[new_row] >= 0) return fail(SDV2_BAD_STATE, "row %d is still occupied", new_row);
-        HIP_TRY(hipMemcpyAsync(sb->x_pipe + (size_t)new_row * sb->row_floats, x_in_dev, row_bytes, hipMemcpyDeviceToDevice, s),
+        HIP_TRY(hipMemcpyAsync(sb->x_pipe + (size_t)new_row * row_floats, in_dev, row_bytes, hipMemcpyDeviceToDevice, s),
                 "copy of the entering chunk");
         sb->depth[new_row] = 0;
         sb->frame_pos0[new_row] = frame_pos0;
@@ -1654,14 +1651,17 @@ int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg,
         while (r1 < n && sb->depth[r1] >= 0) ++r1;
         const int B = r1 - r;
         sdv2_chunk_desc descs[SDV2_MAX_BATCH];
-        float ts[SDV2_MAX_BATCH];
+        float lv[SDV2_MAX_BATCH], lv_next[SDV2_MAX_BATCH];
+        bool need_eps = false;
         for (int b = 0; b < B; ++b) {
             const int d = sb->depth[r + b];
             descs[b].stream_id = sb->cache_ids[d];
             descs[b].frame_pos0 = sb->frame_pos0[r + b];
             descs[b].n_frames = sb->n_frames;
             descs[b].advance = 1;
-            ts[b] = timesteps_host[d];
+            lv[b] = level[d];
+            lv_next[b] = io ? level[d + 1] : 0.0f;
+            need_eps = need_eps || lv_next[b] > 0.0f;
         }
         kt.assign((size_t)cfg->n_layers * B, nullptr);
         vtt.assign((size_t)cfg->n_layers * B, nullptr);
@@ -1670,8 +1670,28 @@ int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg,
                 kt[(size_t)layer * B + b] = kt_dev[layer];
                 vtt[(size_t)layer * B + b] = vtt_dev[layer];
             }
-        const int32_t rc = sdv2_denoise_step(cfg, mw, cache, sb->x_pipe + (size_t)r * sb->row_floats, ts, nullptr, kt.data(),
-                                             vtt.data(), descs, B, workspace_dev, workspace_bytes, hip_stream);
+        int32_t rc = SDV2_OK;
+        float* rows_ptr = sb->x_pipe + (size_t)r * row_floats;
+        if (!io) {
+            rc = sdv2_denoise_step(cfg, mw, cache, rows_ptr, lv, nullptr, kt.data(), vtt.data(), descs, B, workspace_dev,
+                                   workspace_bytes, hip_stream);
+        } else {
+            if (need_eps) {                           // the noise of each depth, in the order of the rows of this run
+                for (int b = 0; b < B; ++b) {
+                    if (!(lv_next[b] > 0.0f)) continue;
+                    const hipError_t e = hipMemcpyAsync(eps_rows_dev + (size_t)b * row_floats,
+                                                        eps_by_depth_dev + (size_t)sb->depth[r + b] * row_floats, row_bytes,
+                                                        hipMemcpyDeviceToDevice, s);
+                    if (e != hipSuccess) {
+                        rc = fail(SDV2_HIP_ERROR, "copy of the noise of depth %d: %s", sb->depth[r + b], hipGetErrorString(e));
+                        break;
+                    }
+                }
+            }
+            if (!rc)
+                rc = sdv2_denoise_latents_step(cfg, mw, io, cache, rows_ptr, need_eps ? eps_rows_dev : nullptr, nullptr, lv, lv_next,
+                                               kt.data(), vtt.data(), descs, B, workspace_dev, workspace_bytes, hip_stream);
+        }
         if (rc) {
             if (rows == 0 && new_row >= 0) {          // nothing has run: take the entering chunk out again
                 sb->depth[new_row] = -1;
@@ -1688,7 +1708,7 @@ int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg,
     *emitted_out = 0;
     for (int row = 0; row < n; ++row) {
         if (sb->depth[row] == n) {                    // finished its last step: the clean latent of this micro-step
-            HIP_TRY(hipMemcpyAsync(x_out_dev, sb->x_pipe + (size_t)row * sb->row_floats, row_bytes, hipMemcpyDeviceToDevice, s),
+            HIP_TRY(hipMemcpyAsync(out_dev, sb->x_pipe + (size_t)row * row_floats, row_bytes, hipMemcpyDeviceToDevice, s),
                     "copy of the finished chunk");
             sb->depth[row] = -1;
             *emitted_out = 1;
@@ -1696,6 +1716,91 @@ int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg,
     }
     if (rows_out) *rows_out = rows;
     return SDV2_OK;
+}
+
+// the checks the two kinds of step share; returns 0 or the error
+int32_t stream_batch_check(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw, sdv2_kv_cache* cache,
+                           const float* in_dev, int32_t frame_pos0, const void* const* kt_dev, const void* const* vtt_dev,
+                           int mode) {
+    if (!sb) return fail(SDV2_INVALID_ARG, "handle is null");
+    if (sb->broken) return fail(SDV2_BAD_STATE, "an earlier micro-step failed half way: reset the pipeline and the caches");
+    if (sb->mode != 0 && sb->mode != mode)
+        return fail(SDV2_BAD_STATE, "the pipeline holds %s: reset it before stepping it with the other kind of row",
+                    sb->mode == 1 ? "hidden states" : "latents");
+    const char* why;
+    if (!model_cfg_ok(cfg, &why)) return fail(SDV2_INVALID_ARG, "%s", why);
+    if (!mw || !cache || !kt_dev || !vtt_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    if ((size_t)sb->n_frames * cfg->grid_h * cfg->grid_w * cfg->C != sb->row_floats)
+        return fail(SDV2_INVALID_ARG, "cfg differs from the one the pipeline was created with");
+    if (in_dev && frame_pos0 < 0) return fail(SDV2_INVALID_ARG, "frame_pos0 < 0");
+    for (int d = 0; d < sb->n_steps; ++d)
+        if (sb->cache_ids[d] >= cache->cfg.n_streams) return fail(SDV2_INVALID_ARG, "cache stream %d of depth %d out of range", sb->cache_ids[d], d);
+    for (int layer = 0; layer < cfg->n_layers; ++layer)
+        if (!kt_dev[layer] || !vtt_dev[layer]) return fail(SDV2_INVALID_ARG, "text K/V of layer %d is null", layer);
+    return SDV2_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t sdv2_stream_batch_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw,
+                               sdv2_kv_cache* cache, const float* x_in_dev, int32_t frame_pos0,
+                               const float* timesteps_host, const void* const* kt_dev, const void* const* vtt_dev,
+                               float* x_out_dev, int32_t* emitted_out, int32_t* rows_out, void* workspace_dev,
+                               size_t workspace_bytes, void* hip_stream) {
+    const int32_t bad = stream_batch_check(sb, cfg, mw, cache, x_in_dev, frame_pos0, kt_dev, vtt_dev, 1);
+    if (bad) return bad;
+    if (!timesteps_host || !x_out_dev || !emitted_out || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    const int L = sb->n_frames * cfg->grid_h * cfg->grid_w;
+    const size_t need = sdv2_denoise_workspace_bytes(cfg, sb->n_steps, L);
+    if (workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    const int32_t rc = stream_batch_step_impl(sb, cfg, mw, nullptr, cache, x_in_dev, frame_pos0, timesteps_host, nullptr, nullptr,
+                                              kt_dev, vtt_dev, x_out_dev, emitted_out, rows_out, workspace_dev, workspace_bytes,
+                                              hip_stream);
+    if (!rc) sb->mode = 1;
+    return rc;
+}
+
+size_t sdv2_stream_batch_latents_workspace_bytes(const sdv2_model_cfg* cfg, int32_t n_steps, int32_t n_frames) {
+    const char* why;
+    if (!model_cfg_ok(cfg, &why) || n_steps < 1 || n_steps > SDV2_MAX_BATCH || n_frames < 1) {
+        fail(SDV2_INVALID_ARG, "bad cfg, n_steps or n_frames");
+        return 0;
+    }
+    const int L = n_frames * cfg->grid_h * cfg->grid_w;
+    const size_t step = sdv2_denoise_latents_workspace_bytes(cfg, n_steps, L);
+    if (!step) return 0;
+    return step + align_up((size_t)n_steps * 4 * kLatentChannels * L * sizeof(float), 256);
+}
+
+int32_t sdv2_stream_batch_latents_step(sdv2_stream_batch* sb, const sdv2_model_cfg* cfg, const sdv2_model_weights* mw,
+                                       const sdv2_io_weights* io, sdv2_kv_cache* cache, const float* z_in_dev,
+                                       int32_t frame_pos0, const float* sigmas_host, const float* eps_by_depth_dev,
+                                       const void* const* kt_dev, const void* const* vtt_dev, float* z_out_dev,
+                                       int32_t* emitted_out, int32_t* rows_out, void* workspace_dev, size_t workspace_bytes,
+                                       void* hip_stream) {
+    const int32_t bad = stream_batch_check(sb, cfg, mw, cache, z_in_dev, frame_pos0, kt_dev, vtt_dev, 2);
+    if (bad) return bad;
+    if (!io_weights_ok(io)) return fail(SDV2_INVALID_ARG, "bad io weights");
+    if (!sigmas_host || !z_out_dev || !emitted_out || !workspace_dev) return fail(SDV2_INVALID_ARG, "null pointer");
+    const int n = sb->n_steps;
+    bool any_noise = false;
+    for (int d = 0; d <= n; ++d) {
+        const float sg = sigmas_host[d];
+        if (!(sg >= 0.0f && sg <= 1.0f) || (d < n && !(sg > 0.0f)) || (d > 0 && !(sg <= sigmas_host[d - 1])))
+            return fail(SDV2_INVALID_ARG, "noise levels must fall from at most 1 to at least 0, all but the last above 0 (level %d)", d);
+        any_noise = any_noise || (d > 0 && sg > 0.0f);
+    }
+    if (any_noise && !eps_by_depth_dev) return fail(SDV2_INVALID_ARG, "a level after the first is above 0 but eps_by_depth_dev is null");
+    const size_t need = sdv2_stream_batch_latents_workspace_bytes(cfg, n, sb->n_frames);
+    if (!need || workspace_bytes < need) return fail(SDV2_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, need);
+    const int L = sb->n_frames * cfg->grid_h * cfg->grid_w;
+    const size_t step_ws = sdv2_denoise_latents_workspace_bytes(cfg, n, L);
+    float* eps_rows = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace_dev) + step_ws);
+    const int32_t rc = stream_batch_step_impl(sb, cfg, mw, io, cache, z_in_dev, frame_pos0, sigmas_host, eps_by_depth_dev, eps_rows,
+                                              kt_dev, vtt_dev, z_out_dev, emitted_out, rows_out, workspace_dev, step_ws, hip_stream);
+    if (!rc) sb->mode = 2;
+    return rc;
 }
 
 }  // extern "C"

@@ -111,3 +111,113 @@ def test_stream_batch_validation():
     assert e.value.code == binding.INVALID_ARG and gpu.state(0, 0) == before
     binding.stream_batch_destroy(sb)
     gpu.close()
+
+
+# ------------------------------------------------------------------------------------------ rows of latents
+def run_latents_both(wl, n_steps, n_chunks, n_layers, sigmas, edit=None):
+    """The same rotation with rows of latents: every micro-step one batched sdv2_denoise_latents_step on the GPU;
+    the oracle advances the in-flight chunks one by one with oracle.denoise_latents_step on per-depth caches.
+    Returns the errors of the emitted latents, each relative to the emitted latent and to what the steps changed."""
+    assert len(sigmas) == n_steps + 1
+    gpu = GpuRunner(wl, n_layers=n_layers, n_streams=n_steps, edit=edit)
+    ora = OracleRunner(wl, n_layers=n_layers, n_streams=n_steps, edit=edit)
+    io_np = wk.to_numpy(wk.io_weights(wl))
+    io = gpu.io()
+    kt = binding.ptr_array([gpu.kt[layer][0] for layer in range(n_layers)])
+    vtt = binding.ptr_array([gpu.vtt[layer][0] for layer in range(n_layers)])
+    rows = torch.empty(binding.stream_batch_rows_bytes(gpu.cfg, n_steps, wl.frames_per_chunk), dtype=torch.uint8,
+                       device=gpu.device)
+    sb = binding.stream_batch_create(gpu.cfg, n_steps, list(range(n_steps)), wl.frames_per_chunk, rows)
+    ws = torch.empty(binding.stream_batch_latents_workspace_bytes(gpu.cfg, n_steps, wl.frames_per_chunk), dtype=torch.uint8,
+                     device=gpu.device)
+    noise = lambda chunk, depth: wk.latent_chunk(wl, chunk, 0, kind=2 + depth)     # mixed in after the step at `depth`
+    z_out = torch.empty_like(noise(0, 0)).to(gpu.device)
+
+    def step_fn(z, depth, chunk):
+        z_next, _ = oracle.denoise_latents_step(
+            z, sigmas[depth], sigmas[depth + 1], noise(chunk, depth).double().numpy(), ora.mw, io_np,
+            [ora.layers[l] for l in range(n_layers)], [ora.caches[l][depth] for l in range(n_layers)],
+            [ora.text[l][0][0] for l in range(n_layers)], [ora.text[l][0][1] for l in range(n_layers)], wl.H, wl.grid_h,
+            wl.grid_w, chunk * wl.frames_per_chunk, advance=True)
+        return z_next
+
+    pipe = oracle.StreamBatch(n_steps, step_fn)
+    entered = {}
+    errs, errs_change = [], []
+    for m in range(n_chunks + n_steps - 1):
+        entering = m < n_chunks
+        z_in_np = None
+        z_in = None
+        if entering:
+            clean, eps0 = wk.latent_chunk(wl, m, 0), wk.latent_chunk(wl, m, 0, kind=1)
+            z_in = torch.empty_like(clean).to(gpu.device)
+            binding.noise_latents(clean.to(gpu.device).unsqueeze(0).contiguous(), eps0.to(gpu.device).unsqueeze(0).contiguous(),
+                                  z_in.unsqueeze(0), [sigmas[0]])
+            z_in_np = oracle.noise_latents(clean.double().numpy(), eps0.double().numpy(), sigmas[0])
+            entered[m] = z_in_np
+        # the noise of depth d at this micro-step belongs to the chunk that sits at depth d: chunk m - d
+        eps = torch.stack([noise(max(m - d, 0), d) for d in range(n_steps)]).to(gpu.device).contiguous()
+        emitted, n_rows = binding.stream_batch_latents_step(sb, gpu.cfg, gpu.mw, io, gpu.cache, z_in, m * wl.frames_per_chunk,
+                                                            list(sigmas), eps, kt, vtt, z_out, ws)
+        torch.cuda.synchronize()
+        want_rows, fin = pipe.micro_step(z_in_np, m if entering else None)
+        assert n_rows == want_rows, (m, n_rows, want_rows)
+        assert emitted == (fin is not None), m
+        if fin is not None:
+            chunk, want = fin
+            got = z_out.cpu().numpy()
+            errs.append(max_rel_err(got, want))
+            errs_change.append(max_rel_err(got - entered[chunk], want - entered[chunk]))
+        for d in range(n_steps):
+            for layer in range(n_layers):
+                assert gpu.state(layer, d) == ora.caches[layer][d].state(), (m, d, layer)
+    assert len(errs) == n_chunks
+    binding.stream_batch_destroy(sb)
+    gpu.close()
+    return errs, errs_change
+
+
+@pytest.mark.parametrize("n_steps,sigmas", [(1, (1.0, 0.0)), (2, (1.0, 0.5, 0.0)), (4, (1.0, 0.75, 0.5, 0.25, 0.0))])
+def test_tiny_stream_batch_of_latents(n_steps, sigmas):
+    """Two-block tiny model, six chunks (the depth caches evict), pipeline filled, run and drained; the chunk that
+    leaves is the clean latent."""
+    wl = wk.WORKLOADS["tiny"]
+    errs, errs_change = run_latents_both(wl, n_steps, 6, 2, sigmas, edit=visible_branches(wl))
+    assert max(errs) <= TOL_X, errs
+    assert max(errs_change) <= TOL_X, errs_change
+
+
+def test_stream_batch_of_latents_refusals():
+    wl = wk.WORKLOADS["tiny"]
+    gpu = GpuRunner(wl, n_layers=1, n_streams=2)
+    io = gpu.io()
+    rows = torch.empty(binding.stream_batch_rows_bytes(gpu.cfg, 2, 1), dtype=torch.uint8, device=gpu.device)
+    sb = binding.stream_batch_create(gpu.cfg, 2, [0, 1], 1, rows)
+    kt, vtt = binding.ptr_array([gpu.kt[0][0]]), binding.ptr_array([gpu.vtt[0][0]])
+    z = wk.latent_chunk(wl, 0).to(gpu.device).contiguous()
+    eps = torch.stack([wk.latent_chunk(wl, 0, kind=2), wk.latent_chunk(wl, 0, kind=3)]).to(gpu.device).contiguous()
+    z_out = torch.empty_like(z)
+    ws = torch.empty(binding.stream_batch_latents_workspace_bytes(gpu.cfg, 2, 1), dtype=torch.uint8, device=gpu.device)
+    before = gpu.state(0, 0)
+    for sigmas in ((0.5, 0.75, 0.0), (1.0, 0.0, 0.0), (1.5, 0.5, 0.0)):            # rising; a zero before the end; above 1
+        with pytest.raises(binding.Sdv2Error) as e:
+            binding.stream_batch_latents_step(sb, gpu.cfg, gpu.mw, io, gpu.cache, z, 0, list(sigmas), eps, kt, vtt, z_out, ws)
+        assert e.value.code == binding.INVALID_ARG
+    with pytest.raises(binding.Sdv2Error) as e:                                    # noise needed but missing
+        binding.stream_batch_latents_step(sb, gpu.cfg, gpu.mw, io, gpu.cache, z, 0, [1.0, 0.5, 0.0], None, kt, vtt, z_out, ws)
+    assert e.value.code == binding.INVALID_ARG
+    with pytest.raises(binding.Sdv2Error) as e:
+        binding.stream_batch_latents_step(sb, gpu.cfg, gpu.mw, io, gpu.cache, z, 0, [1.0, 0.5, 0.0], eps, kt, vtt, z_out, ws[:4096])
+    assert e.value.code == binding.WORKSPACE_TOO_SMALL
+    assert gpu.state(0, 0) == before
+    # a handle serves one kind of row until it is reset
+    emitted, n_rows = binding.stream_batch_latents_step(sb, gpu.cfg, gpu.mw, io, gpu.cache, z, 0, [1.0, 0.5, 0.0], eps, kt, vtt, z_out, ws)
+    assert (emitted, n_rows) == (False, 1)
+    x = wk.chunk_input(wl, 1).to(gpu.device).contiguous()
+    with pytest.raises(binding.Sdv2Error) as e:
+        binding.stream_batch_step(sb, gpu.cfg, gpu.mw, gpu.cache, x, 1, [1.0, 2.0], kt, vtt, torch.empty_like(x), gpu.workspace(2, wl.L))
+    assert e.value.code == binding.BAD_STATE
+    binding.stream_batch_reset(sb)
+    torch.cuda.synchronize()
+    binding.stream_batch_destroy(sb)
+    gpu.close()

@@ -200,3 +200,14 @@ def test_latent_io_sizes_and_refusals_on_the_host(lib):
     assert b"io weights" in lib.sdv2_last_error()
     assert lib.sdv2_prof_lds_rates(100, None, 40960, None) == binding.INVALID_ARG
     assert lib.sdv2_prof_lds_rates(100, fake, 1024, None) == binding.INVALID_ARG
+
+
+def test_stream_batch_of_latents_sizes_on_the_host(lib):
+    cfg = binding.model_cfg(512, 4, 2048, 8, 16, 64, 2)
+    L = 8 * 16
+    for n in (1, 2, 4):
+        need = binding.stream_batch_latents_workspace_bytes(cfg, n, 1)
+        assert need >= binding.denoise_latents_workspace_bytes(cfg, n, L) + n * 64 * L * 4
+        # the rows buffer of the handle (hidden states) also holds the latent rows
+        assert binding.stream_batch_rows_bytes(cfg, n, 1) >= n * 64 * L * 4
+    assert binding.stream_batch_latents_workspace_bytes(cfg, 9, 1) == 0
