@@ -242,6 +242,18 @@ def test_wan14b_block_full_size():
     assert max(errs) <= TOL_X, errs
 
 
+@pytest.mark.timeout(600)
+def test_wan14b_block_four_denoising_steps_per_chunk():
+    """One 14B-shaped block, two chunks of four denoising steps each (the first step of a chunk appends, the other
+    three overwrite the same slots), gates of order one."""
+    wl = wk.WORKLOADS["wan14b-step"]
+    res = run_stream_both(wl, n_chunks=2, steps=4, n_layers=1, check_cache=True, cache_chunks=(1,), edit=visible_branches(wl))
+    print("x_err", res["x_err"], flush=True)
+    assert res["state_equal"] and res["slot_map_equal"] and res["ids_equal"]
+    assert max(res["x_err"]) <= TOL_X, res["x_err"]
+    assert max(res["k_err"]) <= 1e-2 and max(res["v_err"]) <= 1e-2
+
+
 @pytest.mark.timeout(900)
 def test_wan14b_step_layers_0_19_39_fed_the_gpu_layer_input():
     """The 40-block 14B-shaped model on chunks 0-3 (warm-up and first eviction in every layer's cache): the library
