@@ -41,6 +41,7 @@ namespace sdv2 {
 namespace {
 
 constexpr int KT = 64;        // keys per tile
+constexpr float kMaxSlack = 8.0f;   // log2 units the row maximum may run ahead of the exponent's reference point
 constexpr int D = kHeadDim;
 constexpr int K_TILE_BYTES = KT * D * 2;
 constexpr int V_TILE_BYTES = D * KT * 2;
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
     for (int i = 0; i < D / 32; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[i][r] = 0.0f;
-    float m_run = -INFINITY;     // running maximum of the scaled (log2-domain) scores of this query
+    float m_run = -INFINITY;     // reference point of this query's exponents: within kMaxSlack below the running maximum of its scaled (log2-domain) scores
     float l_run = 0.0f;          // this lane's share of the running sum
 
     // Half of S^T of the tile in stage sk: d steps 4 half .. 4 half + 3 of both 32-key blocks.  The eight K
@@ -247,14 +248,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
             if (m < 2 * LPT) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
         }
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // rescale only when some row's maximum moved
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        // m_run is the exponent's reference point, not the exact running maximum: it follows the maximum only when that
+        // has grown by more than kMaxSlack (p stays below 2^kMaxSlack, far inside fp32 and bf16 range, and the
+        // reference cancels in O / l), so after the first tiles the accumulators are hardly ever rescaled
+        const bool moved = m_new > m_run + kMaxSlack;
+        if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+            const float alpha = moved ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;
             l_run *= alpha;
 #pragma unroll
             for (int i = 0; i < D / 32; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[i][r] *= alpha;
-            m_run = m_new;
+            m_run = moved ? m_new : m_run;
         }
         // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
         __builtin_amdgcn_sched_barrier(0);
@@ -518,15 +523,15 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // rescale only when some row's maximum moved
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // m_new is finite in every lane that moved
-            const float al = (m_new > m_run || m_run != -INFINITY) ? alpha : 1.0f;   // -inf - -inf is not a number
+        const bool moved = m_new > m_run + kMaxSlack;             // see attention_kernel; false while no key was seen
+        if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+            const float al = moved ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;   // m_new is finite in a lane that moved
             l_run *= al;
 #pragma unroll
             for (int i = 0; i < D / 32; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[i][r] *= al;
-            m_run = m_new;
+            m_run = moved ? m_new : m_run;
         }
         // a wave whose whole slice lies past kv_len in the only tile has seen no key yet: exponent base 0, p = 0
         const float m_use = (tail && m_run == -INFINITY) ? 0.0f : m_run;
