@@ -41,7 +41,9 @@ namespace sdv2 {
 namespace {
 
 constexpr int KT = 64;        // keys per tile
-constexpr float kMaxSlack = 8.0f;   // log2 units the row maximum may run ahead of the exponent's reference point
+constexpr float kMaxSlack = 8.0f;   // log2 units within which a query's exponent reference is left where it is
+constexpr float kNoKey = -1.0e30f;  // reference point of a query that has seen no key yet (key-split form)
+constexpr float kSumLimit = 16384.0f;   // a lane's sum of p over one tile (at most 32 keys) beyond this: move the reference
 constexpr int D = kHeadDim;
 constexpr int K_TILE_BYTES = KT * D * 2;
 constexpr int V_TILE_BYTES = D * KT * 2;
@@ -64,6 +66,14 @@ __device__ __forceinline__ float max2_f32(float a, float b) {
 __device__ __forceinline__ float max_xor32(float x) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return max2_f32(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// Makes the compiler hold the fragments in registers at this point of the program (an empty statement that claims to
+// read and write them): conversions to bf16 cannot be moved past it.
+template <int N>
+__device__ __forceinline__ void pin_fragments(bf16x8 (&f)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
 }
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
@@ -198,9 +208,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
     f32x16 s_a[2], s_b[2];
     // one tile: s_cur holds S^T of tile t; S^T of tile t + 1 is formed into s_nxt on the way
     // (tail: compile-time flag of the one tile that has slots past kv_len, so that the others carry no masking code)
-    auto tile_step = [&](auto tail_c, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], int t) {
+    // (par: compile-time parity of t - t0, which picks the stages: their offsets are then immediates of the LDS reads)
+    auto tile_step = [&](auto tail_c, auto par_c, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], int t) {
         constexpr bool tail = decltype(tail_c)::value;
-        const int rel = t - t0;
+        constexpr int rel = decltype(par_c)::value;
         wait_loads();
         barrier();                       // K(t+1) and V(t) have landed; everyone is done with K(t), V(t-1)
         if (tail) {
@@ -217,42 +228,69 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
                 for (int r = 0; r < 16; ++r)
                     if (t * KT + kb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= kv_len) s_cur[kb][r] = -INFINITY;
         }
-        // ---- first half of S^T(t+1) on the matrix unit | row maximum of tile t on the vector unit.  (Past the
-        // last tile this reads a stale stage and the result is dropped: no branch, so that matrix and vector
-        // instructions share a basic block and can be interleaved.)
-        // The loads of K(t+2) and V(t+1) go out between these MFMAs, one each: issued in a burst after the barrier they
+        // ---- S^T(t+1) on the matrix unit in two halves | under each, p = 2^(s c - m_run) of one 32-key block of
+        // tile t on the vector unit, its row sum and its bf16 fragments.  m_run is the exponents' reference point, not
+        // the exact running maximum: no maximum is formed here at all.  If a score has run more than about
+        // log2(kSumLimit) ahead of it (or no key has been seen yet: m_run = -inf makes p infinite), this lane's sum of
+        // p leaves the range, and the wave then takes the slow path below, which moves the reference point to the
+        // true maximum, rescales the accumulators and forms p again.  The reference cancels in O / l.
+        // (Past the last tile the matrix unit reads a stale stage and the result is dropped: no branch, so that matrix
+        // and vector instructions share a basic block and can be interleaved.)
+        // The loads of K(t+2) and V(t+1) go out between the first MFMAs, one each: issued in a burst after the barrier they
         // hold every wave of the unit (an issuing wave waits while the LDS pipeline takes in the loads before its own,
         // about 25 clocks each) with the matrix pipe idle.  They are unconditional: past the last tile they fetch it
         // again into a stage that nobody reads, so that matrix, vector and load instructions share a basic block.
+        float ls[4];
+        bf16x8 pf[4];
+        auto exps = [&](int kb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb][r], scale_log2e, -m_run));
+                ls[r & 3] = (kb == 0 && r < 4) ? p : ls[r & 3] + p;     // four independent chains
+                pf[kb * 2 + (r >> 3)][r & 7] = (bf16)p;
+            }
+        };
         __builtin_amdgcn_sched_barrier(0);
         qk_half(s_nxt, sk, 0, [&]() {
             load_k(min(t + 2, t1 - 1), rel & 1);
             load_v(min(t + 1, t1 - 1), (rel + 1) & 1);
         });
-        // four independent chains (a dependent vector instruction waits about twice as long as an independent one)
-        float mc[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            mc[c] = max3_f32(s_cur[0][4 * c], s_cur[1][4 * c], s_cur[0][4 * c + 1]);
-            mc[c] = max3_f32(mc[c], s_cur[1][4 * c + 1], s_cur[0][4 * c + 2]);
-            mc[c] = max3_f32(mc[c], s_cur[1][4 * c + 2], s_cur[0][4 * c + 3]);
-            mc[c] = max2_f32(mc[c], s_cur[1][4 * c + 3]);
-        }
-        float mx = max2_f32(max3_f32(mc[0], mc[1], mc[2]), mc[3]);
-        mx = max_xor32(mx);
-        const float m_new = fmaxf(m_run, mx * scale_log2e);     // finite: every tile has a valid key
+        exps(0);
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);       // the eight fragment reads, then MFMA | load | vector work
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             if (m < 2 * LPT) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
-        // m_run is the exponent's reference point, not the exact running maximum: it follows the maximum only when that
-        // has grown by more than kMaxSlack (p stays below 2^kMaxSlack, far inside fp32 and bf16 range, and the
-        // reference cancels in O / l), so after the first tiles the accumulators are hardly ever rescaled
-        const bool moved = m_new > m_run + kMaxSlack;
-        if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+        __builtin_amdgcn_sched_barrier(0);
+        qk_half(s_nxt, sk, 1, nothing);
+        exps(1);
+        float lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+        pin_fragments(pf);               // the bf16 fragments are formed here, among the MFMAs, not after the branch
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(lsum <= kSumLimit)) != 0, 0)) {
+            // Slow path: move the reference point to the true row maximum (four independent chains; the same for the
+            // two lanes of a query), rescale the accumulators and form p again.
+            float mc[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                mc[c] = max3_f32(s_cur[0][4 * c], s_cur[1][4 * c], s_cur[0][4 * c + 1]);
+                mc[c] = max3_f32(mc[c], s_cur[1][4 * c + 1], s_cur[0][4 * c + 2]);
+                mc[c] = max3_f32(mc[c], s_cur[1][4 * c + 2], s_cur[0][4 * c + 3]);
+                mc[c] = max2_f32(mc[c], s_cur[1][4 * c + 3]);
+            }
+            const float mx = max_xor32(max2_f32(max3_f32(mc[0], mc[1], mc[2]), mc[3]));
+            const float m_new = fmaxf(m_run, mx * scale_log2e);     // finite: every tile has a valid key
+            const bool moved = m_new > m_run + kMaxSlack;            // a query within kMaxSlack of its reference keeps it
             const float alpha = moved ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;
             l_run *= alpha;
 #pragma unroll
@@ -260,30 +298,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[i][r] *= alpha;
             m_run = moved ? m_new : m_run;
+            exps(0);
+            exps(1);
+            lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+            pin_fragments(pf);
         }
-        // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
-        __builtin_amdgcn_sched_barrier(0);
-        qk_half(s_nxt, sk, 1, nothing);
-        float ls[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        bf16x8 pf[4];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[kb][r], scale_log2e, -m_run));
-                ls[r & 3] += p;
-                pf[kb * 2 + (r >> 3)][r & 7] = (bf16)p;
-            }
-        }
-        const float lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
         l_run += lsum;
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);
-            __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
-        }
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- O^T += V^T P^T : four steps of 16 keys; step ts uses registers 8 (ts % 2) .. + 7 of block ts / 2,
@@ -321,16 +341,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attention_kernel(Att
     const int t_full = (t1 - 1 == tail_tile) ? t1 - 1 : t1;          // tiles [t0, t_full) have 64 valid slots
     const std::false_type no_tail;
     const std::true_type with_tail;
+    const std::integral_constant<int, 0> even;
+    const std::integral_constant<int, 1> odd;
     int t = t0;
     for (; t + 2 <= t_full; t += 2) {
-        tile_step(no_tail, s_a, s_b, t);
-        tile_step(no_tail, s_b, s_a, t + 1);
+        tile_step(no_tail, even, s_a, s_b, t);
+        tile_step(no_tail, odd, s_b, s_a, t + 1);
     }
     if (t < t_full) {
-        tile_step(no_tail, s_a, s_b, t);
-        if (t_full < t1) tile_step(with_tail, s_b, s_a, t_full);
+        tile_step(no_tail, even, s_a, s_b, t);
+        if (t_full < t1) tile_step(with_tail, odd, s_b, s_a, t_full);
     } else if (t_full < t1) {
-        tile_step(with_tail, s_a, s_b, t_full);
+        tile_step(with_tail, even, s_a, s_b, t_full);
     }
 
     // ---- finish: divide by the row sum and write
@@ -467,7 +489,7 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
     for (int i = 0; i < D / 32; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[i][r] = 0.0f;
-    float m_run = -INFINITY;
+    float m_run = kNoKey;        // finite: a fully masked slice has scores of -inf, and -inf + inf is not a number
     float l_run = 0.0f;
 
     // Half of S^T of this wave's 32 keys of the tile in stage sk: d steps 4 half .. 4 half + 3.
@@ -491,69 +513,81 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
     };
 
     f32x16 s_a, s_b;
-    auto tile_step = [&](auto tail_c, f32x16& s_cur, f32x16& s_nxt, int t) {
+    auto tile_step = [&](auto tail_c, auto par_c, f32x16& s_cur, f32x16& s_nxt, int t) {
         constexpr bool tail = decltype(tail_c)::value;
+        constexpr int par = decltype(par_c)::value;      // parity of t, at compile time: stage offsets become immediates
         wait_loads();
         barrier();                       // K(t+1) and V(t) have landed; everyone is done with K(t), V(t-1)
         if (tail) {
-            blank_v_tail(t, t & 1);
+            blank_v_tail(t, par);
             __syncthreads();
         }
-        if (t + 2 < n_tiles) load_k(t + 2, t & 1);
-        if (t + 1 < n_tiles) load_v(t + 1, (t + 1) & 1);
-        const unsigned char* sk = k_stage + ((t + 1) & 1) * K_BYTES;
-        const unsigned char* sv = v_stage + (t & 1) * V_BYTES;
+        if (t + 2 < n_tiles) load_k(t + 2, par);
+        if (t + 1 < n_tiles) load_v(t + 1, par ^ 1);
+        const unsigned char* sk = k_stage + (par ^ 1) * K_BYTES;
+        const unsigned char* sv = v_stage + par * V_BYTES;
         if (tail) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 if (t * KTT + kw * 32 + 8 * (r >> 2) + 4 * lh + (r & 3) >= kv_len) s_cur[r] = -INFINITY;
         }
-        // ---- first half of S^T(t+1) on the matrix unit | row maximum of tile t on the vector unit
+        // ---- S^T(t+1) on the matrix unit in two halves | p of tile t on the vector unit, without a row maximum
+        // (see attention_kernel): the slow path is taken when a sum of p has left the range, which is also what
+        // happens at a lane's first valid key (m_run = kNoKey: p infinite).  A lane whose slice lies past kv_len has
+        // scores of -inf, p = 0 and keeps kNoKey (finite, so that -inf - m_run is not "not a number").
+        float ls[4];
+        bf16x8 pf[2];
+        auto exps = [&](int h) {
+#pragma unroll
+            for (int r = 8 * h; r < 8 * h + 8; ++r) {
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[r], scale_log2e, -m_run));
+                ls[r & 3] = r < 4 ? p : ls[r & 3] + p;
+                pf[r >> 3][r & 7] = (bf16)p;
+            }
+        };
         __builtin_amdgcn_sched_barrier(0);
         qk_half(s_nxt, sk, 0);
-        float mc[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) mc[c] = max2_f32(max3_f32(s_cur[4 * c], s_cur[4 * c + 1], s_cur[4 * c + 2]), s_cur[4 * c + 3]);
-        float mx = max2_f32(max3_f32(mc[0], mc[1], mc[2]), mc[3]);
-        mx = max_xor32(mx);
-        const float m_new = fmaxf(m_run, mx * scale_log2e);
+        exps(0);
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
-        const bool moved = m_new > m_run + kMaxSlack;             // see attention_kernel; false while no key was seen
-        if (__builtin_amdgcn_ballot_w64(moved) != 0) {
-            const float al = moved ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;   // m_new is finite in a lane that moved
+        __builtin_amdgcn_sched_barrier(0);
+        qk_half(s_nxt, sk, 1);
+        exps(1);
+        float lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+        pin_fragments(pf);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(lsum <= kSumLimit)) != 0, 0)) {
+            float mc[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) mc[c] = max2_f32(max3_f32(s_cur[4 * c], s_cur[4 * c + 1], s_cur[4 * c + 2]), s_cur[4 * c + 3]);
+            const float mx = max_xor32(max2_f32(max3_f32(mc[0], mc[1], mc[2]), mc[3]));
+            const float m_new = fmaxf(m_run, mx * scale_log2e);       // stays kNoKey in a lane that has still seen no key
+            const bool moved = m_new > m_run + kMaxSlack;
+            const float al = moved ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;
             l_run *= al;
 #pragma unroll
             for (int i = 0; i < D / 32; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[i][r] *= al;
             m_run = moved ? m_new : m_run;
+            exps(0);
+            exps(1);
+            lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+            pin_fragments(pf);
         }
-        // a wave whose whole slice lies past kv_len in the only tile has seen no key yet: exponent base 0, p = 0
-        const float m_use = (tail && m_run == -INFINITY) ? 0.0f : m_run;
-        // ---- second half of S^T(t+1) | p = 2^(s c - m) of tile t, its row sum, its bf16 fragments
-        __builtin_amdgcn_sched_barrier(0);
-        qk_half(s_nxt, sk, 1);
-        float ls[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        bf16x8 pf[2];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[r], scale_log2e, -m_use));
-            ls[r & 3] += p;
-            pf[r >> 3][r & 7] = (bf16)p;
-        }
-        l_run += (ls[0] + ls[1]) + (ls[2] + ls[3]);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);
-            __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);
-        }
+        l_run += lsum;
         __builtin_amdgcn_sched_barrier(0);
         // ---- O^T += V^T P^T: two steps of 16 keys; chunk 4 kw + 2 ts + lh of the V^T row in the cache's column order
 #pragma unroll
@@ -584,16 +618,18 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
     const int t_full = (tail_tile >= 0) ? n_tiles - 1 : n_tiles;        // tiles [0, t_full) have 128 valid slots
     const std::false_type no_tail;
     const std::true_type with_tail;
+    const std::integral_constant<int, 0> even;
+    const std::integral_constant<int, 1> odd;
     int t = 0;
     for (; t + 2 <= t_full; t += 2) {
-        tile_step(no_tail, s_a, s_b, t);
-        tile_step(no_tail, s_b, s_a, t + 1);
+        tile_step(no_tail, even, s_a, s_b, t);
+        tile_step(no_tail, odd, s_b, s_a, t + 1);
     }
     if (t < t_full) {
-        tile_step(no_tail, s_a, s_b, t);
-        if (t_full < n_tiles) tile_step(with_tail, s_b, s_a, t_full);
+        tile_step(no_tail, even, s_a, s_b, t);
+        if (t_full < n_tiles) tile_step(with_tail, odd, s_b, s_a, t_full);
     } else if (t_full < n_tiles) {
-        tile_step(with_tail, s_a, s_b, t_full);
+        tile_step(with_tail, even, s_a, s_b, t_full);
     }
 
     // ---- merge the NKW partial results of each query block through LDS (the stages are free now)
@@ -607,16 +643,15 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
         xl[wave * 32 + l31] = l_tot;
     }
     __syncthreads();
-    float mmax = -INFINITY;
+    // a slice that saw no key has m = kNoKey and l = 0: weight 2^(kNoKey - mmax) = 0, or 1 times l = 0 if all are such
+    float mmax = kNoKey;
 #pragma unroll
     for (int k = 0; k < NKW; ++k) mmax = fmaxf(mmax, xm[(qb + NQ * k) * 32 + l31]);
     float lsum = 0.0f;
 #pragma unroll
-    for (int k = 0; k < NKW; ++k) {
-        const float mk = xm[(qb + NQ * k) * 32 + l31];
-        lsum += mk == -INFINITY ? 0.0f : xl[(qb + NQ * k) * 32 + l31] * __builtin_amdgcn_exp2f(mk - mmax);
-    }
-    const float wgt = (m_run == -INFINITY || !(lsum > 0.0f)) ? 0.0f : __builtin_amdgcn_exp2f(m_run - mmax) / lsum;
+    for (int k = 0; k < NKW; ++k)
+        lsum += xl[(qb + NQ * k) * 32 + l31] * __builtin_amdgcn_exp2f(xm[(qb + NQ * k) * 32 + l31] - mmax);
+    const float wgt = lsum > 0.0f ? __builtin_amdgcn_exp2f(m_run - mmax) / lsum : 0.0f;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
