@@ -8,6 +8,7 @@ probabilities to bf16 before the second product.  Bars: 1e-2 of the largest outp
 """
 
 
+import math
 import numpy as np
 import pytest
 import torch
@@ -212,6 +213,58 @@ def test_attention_matches_oracle(B, L, H, kv_lens, splits, waves):
     for b in range(B):
         err = max_rel_err(got[b], want[b])
         assert err < 1e-2, (b, err)
+
+
+# Score profiles along the key index, in log2 units of the exponent (what the kernel's running reference point is
+# measured in).  The kernels keep that reference only loosely behind the row maximum and form no maximum in the
+# steady state, so these walk through every way the reference has to move: maxima that keep growing across tiles,
+# one key far above everything seen, scores far above and far below zero from the first key on, maxima that only fall.
+SCORE_PROFILES = {
+    "growing": lambda j, n: 100.0 * j / n,
+    "falling": lambda j, n: 100.0 * (1.0 - j / n),
+    "spike": lambda j, n: np.where(j == n // 2 + 3, 200.0, 0.0),
+    "huge": lambda j, n: 300.0 + 5.0 * np.sin(j),
+    "far below zero": lambda j, n: -300.0 + 5.0 * np.sin(j),
+    "steps": lambda j, n: 20.0 * (j // 90),
+}
+
+
+@pytest.mark.parametrize("waves,splits", [(0, 0), (4, 0), (8, 0), (2, 0), (4, 3)])
+@pytest.mark.parametrize("profile", sorted(SCORE_PROFILES))
+def test_attention_score_ranges(profile, waves, splits):
+    """q_i = a_i u + noise, k_j = b_j u + noise with u in {-1, +1}^128, so that the scaled score of (i, j) in log2 units is
+    about a_i T(j): a_i runs from 0.5 to 1.5 over the queries and is negated for every third query (its profile is
+    mirrored), so the lanes of a wave need their reference moved at different tiles, and some never."""
+    L, H, D, n = 96, 2, 128, 700
+    Cw = H * D
+    g = torch.Generator().manual_seed(77)
+    u = (torch.randint(0, 2, (H, D), generator=g) * 2 - 1).to(torch.float32)
+    per_unit = math.sqrt(D) * math.log2(math.e)          # log2-domain score of a = b = 1
+    j = np.arange(n)
+    b_j = torch.tensor(np.asarray(SCORE_PROFILES[profile](j, n), dtype=np.float64) / per_unit, dtype=torch.float32)
+    a_i = 0.5 + torch.arange(L, dtype=torch.float32) / L
+    a_i[::3] *= -1.0
+    q = (a_i[:, None, None] * u[None] + 0.1 * torch.randn(L, H, D, generator=g)).to(torch.bfloat16).reshape(1, L, Cw)
+    k_rows = (b_j[:, None, None] * u[None] + 0.1 * torch.randn(n, H, D, generator=g)).to(torch.bfloat16).reshape(n, Cw)
+    v_rows = bf16_randn((n, Cw), 78)
+    cap = (n + 127) // 128 * 128
+    K, VT = pack_kv(k_rows, v_rows, H, cap)
+    want = oracle.attention_dense(f64(q[0]).reshape(L, H, D), f64(k_rows).reshape(n, H, D),
+                                  f64(v_rows).reshape(n, H, D)).reshape(L, Cw)
+    o = torch.full((1, L, Cw), float("nan"), dtype=torch.bfloat16, device=DEV)
+    binding.tuning_set("attn_splits", splits or None)
+    binding.tuning_set("attn_waves", waves or None)
+    try:
+        ws = torch.empty(max(binding.attention_workspace_bytes(1, L, Cw, n), 256), dtype=torch.uint8, device=DEV)
+        binding.attention_bf16(q.to(DEV), [K.to(DEV)], [VT.to(DEV)], [n], [cap], o, H, ws)
+        torch.cuda.synchronize()
+    finally:
+        binding.tuning_set("attn_splits", None)
+        binding.tuning_set("attn_waves", None)
+    got = f64(o)
+    assert np.isfinite(got).all()
+    err = max_rel_err(got[0], want)
+    assert err < 1e-2, err
 
 
 def test_attention_full_size_480p_shape_sampled_queries():
