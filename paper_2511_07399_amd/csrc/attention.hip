@@ -432,7 +432,7 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
     const int b = (int)(logical / (gridDim.x * gridDim.y));
     const int C = a.H * D;
 
-    const int kv_len = a.desc ? a.desc->kv_len[b] : a.kv_len[b];
+    const int kv_len = __builtin_amdgcn_readfirstlane(a.desc ? a.desc->kv_len[b] : a.kv_len[b]);
     const int cap = a.cap[b];
     const int n_tiles = (kv_len + KTT - 1) / KTT;
     const int tail_tile = (kv_len % KTT) ? n_tiles - 1 : -1;
@@ -454,14 +454,16 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
     const int ld_chunk = (lane & 15) ^ (ld_row & 15);                             // 32 i does not change row % 16
     const uint32_t k_off = (uint32_t)ld_row * ROWB + (uint32_t)ld_chunk * 16;
     const size_t v_off = (size_t)ld_row * cap * 2 + (size_t)ld_chunk * 16;
+    // (a tile index past the last tile fetches the last tile again, into a stage that nobody reads any more: the loads
+    // are unconditional so that they can sit among the matrix instructions of a basic block)
     auto load_k = [&](int t, int stage) {
-        const unsigned char* src = kbase + (size_t)t * K_BYTES + k_off;
+        const unsigned char* src = kbase + (size_t)min(t, n_tiles - 1) * K_BYTES + k_off;
         unsigned char* dst = k_stage + stage * K_BYTES + wave * 1024;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) load_to_lds_b128(src + i * (NW * 1024), dst + i * (NW * 1024));
     };
     auto load_v = [&](int t, int stage) {
-        const unsigned char* src = vbase + (size_t)t * (KTT * 2) + v_off;
+        const unsigned char* src = vbase + (size_t)min(t, n_tiles - 1) * (KTT * 2) + v_off;
         unsigned char* dst = v_stage + stage * V_BYTES + wave * 1024;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) load_to_lds_b128(src + (size_t)i * 32 * cap * 2, dst + i * (NW * 1024));
@@ -493,7 +495,15 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
     float l_run = 0.0f;
 
     // Half of S^T of this wave's 32 keys of the tile in stage sk: d steps 4 half .. 4 half + 3.
-    auto qk_half = [&](f32x16& s, const unsigned char* sk, int half) {
+    // this lane's eight K fragments and its two V^T fragments of a step in the first 32-row block, all in stage 0: the
+    // stage and the block add compile-time constants, which the LDS reads take as immediates
+    const unsigned char* kfrag[D / 16];
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) kfrag[i] = k_stage + (kw * 32 + l31) * ROWB + (((2 * i + lh) ^ (l31 & 15)) << 4);
+    const unsigned char* vfrag[2];
+#pragma unroll
+    for (int ts = 0; ts < 2; ++ts) vfrag[ts] = v_stage + l31 * ROWB + (((4 * kw + 2 * ts + lh) ^ (l31 & 15)) << 4);
+    auto qk_half = [&](f32x16& s, int stage, int half, auto&& after_reads) {
         if (half == 0) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.0f;
@@ -501,10 +511,12 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
         bf16x8 kf[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            kf[i] = *reinterpret_cast<const bf16x8*>(sk + (kw * 32 + l31) * ROWB + (((2 * (4 * half + i) + lh) ^ (l31 & 15)) << 4));
+            kf[i] = *reinterpret_cast<const bf16x8*>(kfrag[4 * half + i] + stage * K_BYTES);
+        after_reads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[4 * half + i], s, 0, 0, 0);
     };
+    auto nothing = []() {};
     auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };       // vmcnt(0) only
     auto barrier = [&]() {
         asm volatile("" ::: "memory");
@@ -522,10 +534,7 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
             blank_v_tail(t, par);
             __syncthreads();
         }
-        if (t + 2 < n_tiles) load_k(t + 2, par);
-        if (t + 1 < n_tiles) load_v(t + 1, par ^ 1);
-        const unsigned char* sk = k_stage + (par ^ 1) * K_BYTES;
-        const unsigned char* sv = v_stage + par * V_BYTES;
+        constexpr int sk = par ^ 1;          // stage of K(t+1)
         if (tail) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
@@ -546,17 +555,19 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
             }
         };
         __builtin_amdgcn_sched_barrier(0);
-        qk_half(s_nxt, sk, 0);
+        // the loads of K(t+2) go out between the MFMAs of the first half, those of V(t+1) between those of the second
+        qk_half(s_nxt, sk, 0, [&]() { load_k(t + 2, par); });
         exps(0);
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-        qk_half(s_nxt, sk, 1);
+        qk_half(s_nxt, sk, 1, [&]() { load_v(t + 1, par ^ 1); });
         exps(1);
         float lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
         pin_fragments(pf);
@@ -564,6 +575,7 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
             __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
@@ -594,8 +606,7 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
         for (int ts = 0; ts < 2; ++ts) {
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                const unsigned char* vrow = sv + (db * 32 + l31) * ROWB;
-                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vrow + (((4 * kw + 2 * ts + lh) ^ (l31 & 15)) << 4));
+                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vfrag[ts] + par * V_BYTES + db * 32 * ROWB);
                 o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ts], o_acc[db], 0, 0, 0);
             }
         }
@@ -613,8 +624,8 @@ __global__ __launch_bounds__(64 * NQ * NKW, 1) void attention_ks_kernel(AttnArgs
     if (1 < n_tiles) load_k(1, 1);
     wait_loads();
     barrier();
-    qk_half(s_a, k_stage, 0);
-    qk_half(s_a, k_stage, 1);
+    qk_half(s_a, 0, 0, nothing);
+    qk_half(s_a, 0, 1, nothing);
     const int t_full = (tail_tile >= 0) ? n_tiles - 1 : n_tiles;        // tiles [0, t_full) have 128 valid slots
     const std::false_type no_tail;
     const std::true_type with_tail;
