@@ -26,6 +26,9 @@
 //     matrix unit computes S^T of tile t + 1; the P V product of tile t follows.  The softmax costs about
 //     as many vector cycles as the tile costs matrix cycles, so without this overlap (and that between
 //     the two workgroups of a unit) the matrix unit idles half of the time.
+//   * The exponents' reference point of a query trails its running maximum loosely instead of tracking it: the
+//     steady-state loop forms no row maximum and rescales nothing; a sum of exponentials that leaves the range
+//     sends the wave to a slow path that moves the reference point (it cancels in O / l).
 //   * Skinny launches (few query tiles x heads) split the key range over several workgroups, which
 //     write normalised partial outputs with their (max, sum); a small kernel merges them.
 #include "common.h"
